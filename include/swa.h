@@ -1,0 +1,151 @@
+/*
+ * swa.h -- C ABI of the MI355X (gfx950) Sparse Window Attention decode library.
+ *
+ * The library implements one transformer layer's batched decode-step Sparse
+ * Window Attention (SWA) of ALISA (arXiv 2403.17312, Section IV-B, Algorithm 1)
+ * over a KV cache that lives in device memory, for b sequences x h heads of
+ * head dimension d.  Every (sequence, head) pair is independent.
+ *
+ * Conventions that hold for every entry point unless stated otherwise
+ *   - `swa_params*` is a HOST pointer; every other pointer is a DEVICE pointer
+ *     owned by the caller.  The library never allocates or frees device memory
+ *     and keeps no global state.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
+ *     only enqueue work: they never synchronise and never read device memory on
+ *     the host, so a sequence of calls can be captured into a HIP graph.
+ *   - Return value: SWA_OK (0) or a negative swa_status.  Errors that the host
+ *     can see (null pointers, unsupported shapes) are reported before anything
+ *     is enqueued.  A condition only the device can see (a sequence whose cache
+ *     is full) never writes out of bounds: the affected pairs are skipped and a
+ *     sticky bit is set in the workspace, readable with swa_check_status().
+ *   - Tensors are dense, row-major:
+ *       k_cache, v_cache  [b, h, cap, d]   element type params->dtype
+ *       score             [b, h, cap]      float32 running importance
+ *       pos               [b, h, cap]      int32 original token position
+ *       kept_idx          [b, h, cap]      int32 ascending slot list
+ *       cache_len, seq_len, kept_cnt [b]   int32 (shared by the heads)
+ *     Slot i < cache_len[s] of pair (s, hd) is valid; higher slots are free.
+ *   - Supported shapes: d in {64, 128}; dtype float32, float16 or bfloat16;
+ *     cap <= SWA_MAX_CAP.
+ */
+#ifndef SWA_H_
+#define SWA_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define SWA_MAX_CAP 12288 /* slots per (sequence, head); bounded by LDS per workgroup */
+#define SWA_MAX_PREFILL_ROWS 128
+
+typedef enum { SWA_F32 = 0, SWA_F16 = 1, SWA_BF16 = 2 } swa_dtype;
+
+typedef enum {
+    SWA_OK = 0,
+    SWA_ERR_NULL = -1,              /* a required pointer is NULL */
+    SWA_ERR_BAD_SHAPE = -2,         /* b, h, cap, w or R out of range */
+    SWA_ERR_UNSUPPORTED_D = -3,     /* d not in {64, 128} */
+    SWA_ERR_UNSUPPORTED_DTYPE = -4, /* dtype not a swa_dtype */
+    SWA_ERR_BAD_SPARSITY = -5,      /* sparsity_bp outside 0..9999 */
+    SWA_ERR_CAPACITY = -6,          /* cap above SWA_MAX_CAP, or (status) a cache was full */
+    SWA_ERR_HIP = -7,               /* a HIP runtime call failed */
+    SWA_ERR_ALIGNMENT = -8          /* a row pointer is not 16-byte aligned */
+} swa_status;
+
+typedef struct {
+    int32_t b;           /* sequences */
+    int32_t h;           /* heads */
+    int32_t d;           /* head dimension, 64 or 128 */
+    int32_t cap;         /* slots per (sequence, head) in every cache tensor */
+    int32_t w;           /* local window: the most recent w tokens are always kept (>= 0) */
+    int32_t sparsity_bp; /* KV sparsity in basis points, 0..9999; caching ratio r = 1 - sparsity */
+    int32_t dtype;       /* swa_dtype of q, k_new, v_new, caches, out */
+    float scale;         /* logit scale; 0 selects 1/sqrt(d) (Eq. 1) */
+} swa_params;
+
+/* Message for a swa_status code (static storage, never NULL). */
+const char *swa_strerror(int code);
+
+/* Bytes of device workspace the other calls need for these params (0 on invalid params).
+ * The caller allocates it (256-byte aligned) and calls swa_workspace_init once. */
+size_t swa_workspace_bytes(const swa_params *params);
+
+/* Enqueue a fill that zeroes the workspace (status bits and arrival counters). */
+int swa_workspace_init(const swa_params *params, void *workspace, void *stream);
+
+/* Synchronises `stream`, copies the sticky status bits to the host and clears them.
+ * *status_out = SWA_OK or SWA_ERR_CAPACITY (some decode step met a full cache).
+ * This is the only entry point that blocks. */
+int swa_check_status(const swa_params *params, void *workspace, void *stream, int32_t *status_out);
+
+/*
+ * Budget of Algorithm 1 line 1, generalised to an independent local window.
+ * Host-only helper (no device work): for logical length n and m cached slots,
+ *   keep_raw = nearest integer of n * (1 - sparsity)   (halves round up)
+ *   n_local  = min(w, m)
+ *   keep     = min(m, max(keep_raw, n_local)),  n_global = keep - n_local.
+ * Algorithm 1's even split is the case w = nearest integer of n*r/2.
+ */
+int swa_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp, int32_t *keep,
+               int32_t *n_local, int32_t *n_global);
+
+/*
+ * Prefill importance seed: Algorithm 1 line 2 ("local attention sum")
+ * evaluated at the end of the prompt.  For every pair,
+ *   score[j] = sum over r < R of softmax_causal(q_tail[r] . K^T * scale)[j]
+ * where row r of q_tail is the query at position t = cache_len - R + r and
+ * attends to keys 0..t (Eq. 1 with the causal mask); rows with t < 0 are
+ * ignored.  score[j] = 0 for cache_len <= j < cap.  Runs on MFMA.
+ *   q_tail [b,h,R,d] dtype (in), 1 <= R <= SWA_MAX_PREFILL_ROWS
+ *   k_cache (in), cache_len [b] (in), score (out).
+ */
+int swa_prefill_scores(const swa_params *params, const void *q_tail, int32_t R,
+                       const void *k_cache, const int32_t *cache_len, float *score,
+                       void *workspace, void *stream);
+
+/*
+ * One decode step of Sparse Window Attention for every pair (Section II-A
+ * KV caching; Algorithm 1):
+ *   1. append: k_new, v_new go to slot len = cache_len[s]; pos[len] = seq_len[s]-1;
+ *      score[len] = 0; m = len + 1;
+ *   2. attention weights over the whole cache (Eq. 1): p = softmax(q . K^T * scale)
+ *      over the m slots, fp32;
+ *   3. importance: score[i] += p[i]  (running local attention sum, Alg. 1 line 2);
+ *   4. budget + selection (Alg. 1 lines 1, 3-5): keep/n_local/n_global from
+ *      swa_budget(seq_len[s], m, w, sparsity); kept = the last n_local slots plus
+ *      the n_global earlier slots of largest score (ties: lowest slot);
+ *      kept_idx gets the ascending list, kept_cnt[s] = keep;
+ *   5. output (Alg. 1 lines 6-8): softmax over the kept keys times their
+ *      values, i.e. out = sum_kept p_i v_i / sum_kept p_i, rounded once to dtype.
+ * The cache is left uncompacted; cache_len[s] becomes m.  Calling again without
+ * swa_compact_kv is legal (all m slots stay candidates).
+ *   q, k_new, v_new [b,h,d] (in); k_cache, v_cache, score, pos (in/out);
+ *   cache_len [b] (in/out); seq_len [b] (in) logical length n counting this token;
+ *   kept_idx, kept_cnt, out [b,h,d] (out);
+ *   probs_dbg [b,h,cap] float32 or NULL: receives p (0 beyond m) when given.
+ * A sequence with cache_len[s] + 1 > cap is skipped (nothing written for it)
+ * and the capacity status bit is set.
+ */
+int swa_decode_step(const swa_params *params, const void *q, const void *k_new, const void *v_new,
+                    void *k_cache, void *v_cache, float *score, int32_t *pos, int32_t *cache_len,
+                    const int32_t *seq_len, int32_t *kept_idx, int32_t *kept_cnt, void *out,
+                    float *probs_dbg, void *workspace, void *stream);
+
+/*
+ * In-place compaction of the cache to the kept set (the gather of Algorithm 1
+ * line 6 applied to the cache itself): for every pair, row kept_idx[j] of
+ * k_cache, v_cache, score and pos moves to slot j, j < kept_cnt[s], order
+ * preserved; cache_len[s] = kept_cnt[s].  kept_idx must be ascending (as
+ * swa_decode_step writes it).  Bit-exact copies.
+ */
+int swa_compact_kv(const swa_params *params, void *k_cache, void *v_cache, float *score,
+                   int32_t *pos, const int32_t *kept_idx, const int32_t *kept_cnt,
+                   int32_t *cache_len, void *workspace, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWA_H_ */

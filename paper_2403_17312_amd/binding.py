@@ -1,0 +1,188 @@
+"""Thin ctypes binding of libswa_hip.so (the C ABI declared in include/swa.h).
+
+Argument marshalling only: every step of the decode path runs in the HIP kernels
+behind the C entry points.  PyTorch supplies device memory (tensors) and the
+stream.  There is no fallback: if the library has not been built, or a call
+fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libswa_hip.so")
+
+SWA_F32, SWA_F16, SWA_BF16 = 0, 1, 2
+SWA_OK = 0
+SWA_ERR_NULL, SWA_ERR_BAD_SHAPE, SWA_ERR_UNSUPPORTED_D, SWA_ERR_UNSUPPORTED_DTYPE = -1, -2, -3, -4
+SWA_ERR_BAD_SPARSITY, SWA_ERR_CAPACITY, SWA_ERR_HIP, SWA_ERR_ALIGNMENT = -5, -6, -7, -8
+SWA_MAX_CAP = 12288
+SWA_MAX_PREFILL_ROWS = 128
+
+DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
+EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
+           "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv"]
+
+
+class SwaParams(ctypes.Structure):
+    _fields_ = [("b", ctypes.c_int32), ("h", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("cap", ctypes.c_int32), ("w", ctypes.c_int32), ("sparsity_bp", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+
+
+class SwaError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        super().__init__(f"{what}: {strerror(code)} ({code})")
+
+
+_lib = None
+
+
+def lib():
+    """Loads libswa_hip.so; raises if it has not been built."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -m paper_2403_17312_amd.build` "
+                "(there is no fallback path)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32p = ctypes.c_void_p, ctypes.c_void_p
+        pp = ctypes.POINTER(SwaParams)
+        L.swa_strerror.restype = ctypes.c_char_p
+        L.swa_strerror.argtypes = [ctypes.c_int]
+        L.swa_workspace_bytes.restype = ctypes.c_size_t
+        L.swa_workspace_bytes.argtypes = [pp]
+        L.swa_workspace_init.restype = ctypes.c_int
+        L.swa_workspace_init.argtypes = [pp, vp, vp]
+        L.swa_check_status.restype = ctypes.c_int
+        L.swa_check_status.argtypes = [pp, vp, vp, ctypes.POINTER(ctypes.c_int32)]
+        L.swa_budget.restype = ctypes.c_int
+        L.swa_budget.argtypes = [ctypes.c_int32] * 4 + [ctypes.POINTER(ctypes.c_int32)] * 3
+        L.swa_prefill_scores.restype = ctypes.c_int
+        L.swa_prefill_scores.argtypes = [pp, vp, ctypes.c_int32, vp, i32p, vp, vp, vp]
+        L.swa_decode_step.restype = ctypes.c_int
+        L.swa_decode_step.argtypes = [pp] + [vp] * 15
+        L.swa_compact_kv.restype = ctypes.c_int
+        L.swa_compact_kv.argtypes = [pp] + [vp] * 9
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().swa_strerror(int(code)).decode()
+
+
+def make_params(b: int, h: int, d: int, cap: int, w: int, sparsity_bp: int, dtype,
+                scale: float = 0.0) -> SwaParams:
+    code = DTYPE_CODE[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
+    return SwaParams(b, h, d, cap, w, sparsity_bp, code, scale)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    if t is None:
+        return None
+    if not t.is_contiguous():
+        raise ValueError("tensors handed to the SWA library must be contiguous")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream if hasattr(stream, "cuda_stream") else int(stream))
+
+
+def _check(rc: int, what: str) -> None:
+    if rc != SWA_OK:
+        raise SwaError(rc, what)
+
+
+def swa_workspace_bytes(params: SwaParams) -> int:
+    return int(lib().swa_workspace_bytes(ctypes.byref(params)))
+
+
+def swa_budget(n: int, m: int, w: int, sparsity_bp: int):
+    keep, nl, ng = ctypes.c_int32(), ctypes.c_int32(), ctypes.c_int32()
+    _check(lib().swa_budget(n, m, w, sparsity_bp, ctypes.byref(keep), ctypes.byref(nl),
+                            ctypes.byref(ng)), "swa_budget")
+    return keep.value, nl.value, ng.value
+
+
+def swa_workspace_init(params: SwaParams, workspace: torch.Tensor, stream=None) -> None:
+    _check(lib().swa_workspace_init(ctypes.byref(params), _ptr(workspace), _stream(stream)),
+           "swa_workspace_init")
+
+
+def swa_check_status(params: SwaParams, workspace: torch.Tensor, stream=None) -> int:
+    st = ctypes.c_int32(0)
+    _check(lib().swa_check_status(ctypes.byref(params), _ptr(workspace), _stream(stream),
+                                  ctypes.byref(st)), "swa_check_status")
+    return st.value
+
+
+def swa_prefill_scores(params: SwaParams, q_tail, R: int, k_cache, cache_len, score, workspace,
+                       stream=None) -> None:
+    _check(lib().swa_prefill_scores(ctypes.byref(params), _ptr(q_tail), int(R), _ptr(k_cache),
+                                    _ptr(cache_len), _ptr(score), _ptr(workspace),
+                                    _stream(stream)), "swa_prefill_scores")
+
+
+def swa_decode_step(params: SwaParams, q, k_new, v_new, k_cache, v_cache, score, pos, cache_len,
+                    seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, stream=None) -> None:
+    _check(lib().swa_decode_step(ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                 _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(pos),
+                                 _ptr(cache_len), _ptr(seq_len), _ptr(kept_idx), _ptr(kept_cnt),
+                                 _ptr(out), _ptr(probs_dbg), _ptr(workspace), _stream(stream)),
+           "swa_decode_step")
+
+
+def swa_compact_kv(params: SwaParams, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,
+                   workspace, stream=None) -> None:
+    _check(lib().swa_compact_kv(ctypes.byref(params), _ptr(k_cache), _ptr(v_cache), _ptr(score),
+                                _ptr(pos), _ptr(kept_idx), _ptr(kept_cnt), _ptr(cache_len),
+                                _ptr(workspace), _stream(stream)), "swa_compact_kv")
+
+
+class DecodeState:
+    """Device tensors of one layer's SWA cache (allocation plumbing only)."""
+
+    def __init__(self, params: SwaParams, device="cuda", debug_probs: bool = False):
+        b, h, d, cap = params.b, params.h, params.d, params.cap
+        dt = {v: k for k, v in DTYPE_CODE.items()}[params.dtype]
+        self.params = params
+        self.K = torch.zeros((b, h, cap, d), dtype=dt, device=device)
+        self.V = torch.zeros((b, h, cap, d), dtype=dt, device=device)
+        self.score = torch.zeros((b, h, cap), dtype=torch.float32, device=device)
+        self.pos = torch.full((b, h, cap), -1, dtype=torch.int32, device=device)
+        self.cache_len = torch.zeros((b,), dtype=torch.int32, device=device)
+        self.seq_len = torch.zeros((b,), dtype=torch.int32, device=device)
+        self.kept_idx = torch.full((b, h, cap), -1, dtype=torch.int32, device=device)
+        self.kept_cnt = torch.zeros((b,), dtype=torch.int32, device=device)
+        self.out = torch.zeros((b, h, d), dtype=dt, device=device)
+        self.probs = (torch.zeros((b, h, cap), dtype=torch.float32, device=device)
+                      if debug_probs else None)
+        self.workspace = torch.zeros((swa_workspace_bytes(params),), dtype=torch.uint8,
+                                     device=device)
+        swa_workspace_init(params, self.workspace)
+
+    def decode_step(self, q, k_new, v_new, stream=None) -> None:
+        swa_decode_step(self.params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
+                        self.cache_len, self.seq_len, self.kept_idx, self.kept_cnt, self.out,
+                        self.probs, self.workspace, stream)
+
+    def compact(self, stream=None) -> None:
+        swa_compact_kv(self.params, self.K, self.V, self.score, self.pos, self.kept_idx,
+                       self.kept_cnt, self.cache_len, self.workspace, stream)
+
+    def prefill_scores(self, q_tail, stream=None) -> None:
+        swa_prefill_scores(self.params, q_tail, q_tail.shape[2], self.K, self.cache_len, self.score,
+                           self.workspace, stream)
+
+    def check_status(self, stream=None) -> int:
+        return swa_check_status(self.params, self.workspace, stream)

@@ -1,0 +1,180 @@
+// C-ABI entry points: argument validation on the host, then kernel launches on the
+// caller's stream.  Nothing here allocates, synchronises (except
+// swa_check_status) or reads device memory.
+#include <math.h>
+#include <stdio.h>
+
+#include <mutex>
+#include <unordered_map>
+
+#include "swa_kernels.hpp"
+
+namespace swa {
+
+int ensure_dynamic_lds(const void* kernel, size_t bytes)
+{
+    if (bytes <= 48 * 1024) return SWA_OK;
+    static std::mutex mu;
+    static std::unordered_map<const void*, size_t> granted;
+    std::lock_guard<std::mutex> lock(mu);
+    auto it = granted.find(kernel);
+    if (it != granted.end() && it->second >= bytes) return SWA_OK;
+    if (hipFuncSetAttribute(kernel, hipFuncAttributeMaxDynamicSharedMemorySize, (int)bytes) != hipSuccess) {
+        (void)hipGetLastError();
+        return SWA_ERR_CAPACITY;
+    }
+    granted[kernel] = bytes;
+    return SWA_OK;
+}
+
+int decode_block_threads(int64_t pairs)
+{
+    // 256 CUs: with few pairs per CU a larger workgroup keeps more loads in flight.
+    if (pairs >= 256 * 8) return 256;
+    if (pairs >= 256 * 3) return 512;
+    return 1024;
+}
+
+__global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = 0;
+}
+
+int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stream)
+{
+    const int64_t n = (int64_t)(swa_workspace_bytes(&p) / 4);
+    hipLaunchKernelGGL(swa_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
+                       static_cast<int32_t*>(workspace), n);
+    return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
+}
+
+static int validate(const swa_params* p)
+{
+    if (!p) return SWA_ERR_NULL;
+    if (p->dtype != SWA_F32 && p->dtype != SWA_F16 && p->dtype != SWA_BF16) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (p->d != 64 && p->d != 128) return SWA_ERR_UNSUPPORTED_D;
+    if (p->b < 1 || p->h < 1 || p->cap < 1 || p->w < 0) return SWA_ERR_BAD_SHAPE;
+    if ((int64_t)p->b * p->h > 0x7fffffffLL) return SWA_ERR_BAD_SHAPE;
+    if (p->cap > SWA_MAX_CAP) return SWA_ERR_CAPACITY;
+    if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
+    if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
+    return SWA_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static float effective_scale(const swa_params* p)
+{
+    return p->scale > 0.f ? p->scale : 1.0f / sqrtf((float)p->d);
+}
+
+}  // namespace swa
+
+extern "C" {
+
+const char* swa_strerror(int code)
+{
+    switch (code) {
+        case SWA_OK: return "ok";
+        case SWA_ERR_NULL: return "a required pointer is NULL";
+        case SWA_ERR_BAD_SHAPE: return "b, h, cap, w, scale or R out of range";
+        case SWA_ERR_UNSUPPORTED_D: return "head dimension must be 64 or 128";
+        case SWA_ERR_UNSUPPORTED_DTYPE: return "dtype must be SWA_F32, SWA_F16 or SWA_BF16";
+        case SWA_ERR_BAD_SPARSITY: return "sparsity_bp must be in 0..9999";
+        case SWA_ERR_CAPACITY: return "cap exceeds SWA_MAX_CAP, or a sequence's cache was full";
+        case SWA_ERR_HIP: return "a HIP runtime call failed";
+        case SWA_ERR_ALIGNMENT: return "tensor pointers must be 16-byte aligned";
+        default: return "unknown swa_status";
+    }
+}
+
+size_t swa_workspace_bytes(const swa_params* params)
+{
+    if (swa::validate(params) != SWA_OK) return 0;
+    const size_t bytes = swa::kWsArriveOffset + sizeof(int32_t) * (size_t)params->b;
+    return (bytes + 255) & ~(size_t)255;
+}
+
+int swa_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp, int32_t* keep, int32_t* n_local,
+               int32_t* n_global)
+{
+    if (!keep || !n_local || !n_global) return SWA_ERR_NULL;
+    if (n < 0 || m < 0 || w < 0) return SWA_ERR_BAD_SHAPE;
+    if (sparsity_bp < 0 || sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
+    swa::budget(n, m, w, sparsity_bp, *keep, *n_local, *n_global);
+    return SWA_OK;
+}
+
+int swa_workspace_init(const swa_params* params, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!workspace) return SWA_ERR_NULL;
+    return swa::launch_workspace_init(*params, workspace, static_cast<hipStream_t>(stream));
+}
+
+int swa_check_status(const swa_params* params, void* workspace, void* stream, int32_t* status_out)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!workspace || !status_out) return SWA_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    int32_t bits = 0;
+    char* ws = static_cast<char*>(workspace) + swa::kWsStatusOffset;
+    if (hipMemcpyAsync(&bits, ws, sizeof(bits), hipMemcpyDeviceToHost, st) != hipSuccess) return SWA_ERR_HIP;
+    if (hipStreamSynchronize(st) != hipSuccess) return SWA_ERR_HIP;
+    if (bits != 0) {
+        hipLaunchKernelGGL(swa::swa_fill_zero_kernel, dim3(1), dim3(64), 0, st, reinterpret_cast<int32_t*>(ws),
+                           (int64_t)1);
+        if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
+    }
+    *status_out = (bits & swa::kStatusCapacityBit) ? SWA_ERR_CAPACITY : SWA_OK;
+    return SWA_OK;
+}
+
+int swa_prefill_scores(const swa_params* params, const void* q_tail, int32_t R, const void* k_cache,
+                       const int32_t* cache_len, float* score, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    (void)workspace;
+    if (!q_tail || !k_cache || !cache_len || !score) return SWA_ERR_NULL;
+    if (R < 1 || R > SWA_MAX_PREFILL_ROWS) return SWA_ERR_BAD_SHAPE;
+    if (!swa::aligned16(q_tail) || !swa::aligned16(k_cache)) return SWA_ERR_ALIGNMENT;
+    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, score,
+                               static_cast<hipStream_t>(stream));
+}
+
+int swa_decode_step(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                    void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
+                    const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
+                    float* probs_dbg, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!q || !k_new || !v_new || !k_cache || !v_cache || !score || !pos || !cache_len || !seq_len ||
+        !kept_idx || !kept_cnt || !out || !workspace)
+        return SWA_ERR_NULL;
+    if (!swa::aligned16(q) || !swa::aligned16(k_new) || !swa::aligned16(v_new) || !swa::aligned16(k_cache) ||
+        !swa::aligned16(v_cache) || !swa::aligned16(out))
+        return SWA_ERR_ALIGNMENT;
+    return swa::launch_decode(*params, swa::effective_scale(params), q, k_new, v_new, k_cache, v_cache, score,
+                              pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace,
+                              static_cast<hipStream_t>(stream));
+}
+
+int swa_compact_kv(const swa_params* params, void* k_cache, void* v_cache, float* score, int32_t* pos,
+                   const int32_t* kept_idx, const int32_t* kept_cnt, int32_t* cache_len, void* workspace,
+                   void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    (void)workspace;
+    if (!k_cache || !v_cache || !score || !pos || !kept_idx || !kept_cnt || !cache_len) return SWA_ERR_NULL;
+    if (!swa::aligned16(k_cache) || !swa::aligned16(v_cache)) return SWA_ERR_ALIGNMENT;
+    return swa::launch_compact(*params, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,
+                               static_cast<hipStream_t>(stream));
+}
+
+}  // extern "C"

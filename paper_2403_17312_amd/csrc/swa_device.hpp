@@ -1,0 +1,235 @@
+// Device-side helpers shared by the SWA kernels (gfx950, wave64).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "swa.h"
+
+namespace swa {
+
+constexpr int kWave = 64;
+
+// Workspace layout (device memory supplied by the caller):
+//   int32 status                     sticky error bits
+//   int32 arrive[b]  (at +64 bytes)  per-sequence arrival counters of decode steps
+constexpr size_t kWsStatusOffset = 0;
+constexpr size_t kWsArriveOffset = 64;
+constexpr int32_t kStatusCapacityBit = 1;
+
+struct F32 {};
+struct F16 {};
+struct BF16 {};
+
+typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
+typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef float float4_t __attribute__((ext_vector_type(4)));
+typedef float float16_t __attribute__((ext_vector_type(16)));
+
+// One 16-byte vector of cache elements, as loaded by one lane.
+struct alignas(16) Vec16 {
+    uint32_t x, y, z, w;
+};
+
+template <typename T>
+struct Elem;
+template <>
+struct Elem<F32> {
+    static constexpr int kBytes = 4;
+    static constexpr int kPerVec = 4;
+};
+template <>
+struct Elem<F16> {
+    static constexpr int kBytes = 2;
+    static constexpr int kPerVec = 8;
+};
+template <>
+struct Elem<BF16> {
+    static constexpr int kBytes = 2;
+    static constexpr int kPerVec = 8;
+};
+
+__device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
+__device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uint32_t, f); }
+
+__device__ __forceinline__ float bf16_lo(uint32_t u) { return u2f(u << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t u) { return u2f(u & 0xffff0000u); }
+
+__device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
+{
+    uint32_t u = f2u(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // quiet NaN
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // round to nearest even
+}
+
+__device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
+{
+    _Float16 h = (_Float16)f;
+    return (uint32_t) __builtin_bit_cast(uint16_t, h);
+}
+
+// Widen the elements of one 16-byte vector to fp32.
+template <typename T>
+__device__ __forceinline__ void unpack(const Vec16& v, float* f);
+template <>
+__device__ __forceinline__ void unpack<F32>(const Vec16& v, float* f)
+{
+    f[0] = u2f(v.x); f[1] = u2f(v.y); f[2] = u2f(v.z); f[3] = u2f(v.w);
+}
+template <>
+__device__ __forceinline__ void unpack<F16>(const Vec16& v, float* f)
+{
+    half8_t h = __builtin_bit_cast(half8_t, v);
+#pragma unroll
+    for (int i = 0; i < 8; ++i) f[i] = (float)h[i];
+}
+template <>
+__device__ __forceinline__ void unpack<BF16>(const Vec16& v, float* f)
+{
+    f[0] = bf16_lo(v.x); f[1] = bf16_hi(v.x); f[2] = bf16_lo(v.y); f[3] = bf16_hi(v.y);
+    f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
+}
+
+// Partial dot product of one 16-byte key vector with the matching query vector,
+// fp32 accumulation.  Query operand: the raw vector for F16 (packed dot), the
+// widened fp32 values otherwise.
+template <typename T>
+struct QFrag;
+template <>
+struct QFrag<F32> {
+    float f[4];
+    __device__ __forceinline__ void load(const Vec16& v) { unpack<F32>(v, f); }
+    __device__ __forceinline__ float dot(const Vec16& k, float acc) const
+    {
+        acc = __builtin_fmaf(u2f(k.x), f[0], acc);
+        acc = __builtin_fmaf(u2f(k.y), f[1], acc);
+        acc = __builtin_fmaf(u2f(k.z), f[2], acc);
+        acc = __builtin_fmaf(u2f(k.w), f[3], acc);
+        return acc;
+    }
+};
+template <>
+struct QFrag<F16> {
+    Vec16 raw;
+    __device__ __forceinline__ void load(const Vec16& v) { raw = v; }
+    __device__ __forceinline__ float dot(const Vec16& k, float acc) const
+    {
+        // v_dot2_f32_f16: exact fp16 products, fp32 accumulation
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.x), __builtin_bit_cast(half2_t, raw.x), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.y), __builtin_bit_cast(half2_t, raw.y), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.z), __builtin_bit_cast(half2_t, raw.z), acc, false);
+        acc = __builtin_amdgcn_fdot2(__builtin_bit_cast(half2_t, k.w), __builtin_bit_cast(half2_t, raw.w), acc, false);
+        return acc;
+    }
+};
+template <>
+struct QFrag<BF16> {
+    float f[8];
+    __device__ __forceinline__ void load(const Vec16& v) { unpack<BF16>(v, f); }
+    __device__ __forceinline__ float dot(const Vec16& k, float acc) const
+    {
+        acc = __builtin_fmaf(bf16_lo(k.x), f[0], acc);
+        acc = __builtin_fmaf(bf16_hi(k.x), f[1], acc);
+        acc = __builtin_fmaf(bf16_lo(k.y), f[2], acc);
+        acc = __builtin_fmaf(bf16_hi(k.y), f[3], acc);
+        acc = __builtin_fmaf(bf16_lo(k.z), f[4], acc);
+        acc = __builtin_fmaf(bf16_hi(k.z), f[5], acc);
+        acc = __builtin_fmaf(bf16_lo(k.w), f[6], acc);
+        acc = __builtin_fmaf(bf16_hi(k.w), f[7], acc);
+        return acc;
+    }
+};
+
+// Round fp32 values to the cache dtype and pack them into one 16-byte vector.
+template <typename T>
+__device__ __forceinline__ Vec16 pack(const float* f);
+template <>
+__device__ __forceinline__ Vec16 pack<F32>(const float* f)
+{
+    return Vec16{f2u(f[0]), f2u(f[1]), f2u(f[2]), f2u(f[3])};
+}
+template <>
+__device__ __forceinline__ Vec16 pack<F16>(const float* f)
+{
+    Vec16 v;
+    v.x = f32_to_f16_bits(f[0]) | (f32_to_f16_bits(f[1]) << 16);
+    v.y = f32_to_f16_bits(f[2]) | (f32_to_f16_bits(f[3]) << 16);
+    v.z = f32_to_f16_bits(f[4]) | (f32_to_f16_bits(f[5]) << 16);
+    v.w = f32_to_f16_bits(f[6]) | (f32_to_f16_bits(f[7]) << 16);
+    return v;
+}
+template <>
+__device__ __forceinline__ Vec16 pack<BF16>(const float* f)
+{
+    Vec16 v;
+    v.x = f32_to_bf16_bits(f[0]) | (f32_to_bf16_bits(f[1]) << 16);
+    v.y = f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16);
+    v.z = f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16);
+    v.w = f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16);
+    return v;
+}
+
+__device__ __forceinline__ Vec16 load16(const void* p) { return *reinterpret_cast<const Vec16*>(p); }
+__device__ __forceinline__ void store16(void* p, const Vec16& v) { *reinterpret_cast<Vec16*>(p) = v; }
+
+// ---- wave / block reductions -------------------------------------------------
+
+__device__ __forceinline__ float wave_sum(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+__device__ __forceinline__ float wave_max(float v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+// All threads get the result.  `red` is an LDS array of at least blockDim.x/64 floats.
+// Two barriers; `red` may be reused right after the call returns... by a later
+// call of these helpers only (each call starts with a barrier-protected write).
+template <int NT>
+__device__ __forceinline__ float block_sum(float v, float* red)
+{
+    constexpr int NW = NT / kWave;
+    v = wave_sum(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = 0.f;
+#pragma unroll
+    for (int i = 0; i < NW; ++i) t += red[i];
+    return t;
+}
+template <int NT>
+__device__ __forceinline__ float block_max(float v, float* red)
+{
+    constexpr int NW = NT / kWave;
+    v = wave_max(v);
+    __syncthreads();
+    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
+    __syncthreads();
+    float t = red[0];
+#pragma unroll
+    for (int i = 1; i < NW; ++i) t = fmaxf(t, red[i]);
+    return t;
+}
+
+// Budget of Algorithm 1 line 1 with an independent window (integer arithmetic on
+// basis points so that host and device agree exactly).
+__host__ __device__ __forceinline__ void budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp,
+                                                int32_t& keep, int32_t& n_local, int32_t& n_global)
+{
+    long long keep_raw = ((long long)n * (long long)(10000 - sparsity_bp) + 5000) / 10000;
+    long long wl = w < m ? w : m;
+    long long k = keep_raw > wl ? keep_raw : wl;
+    if (k > m) k = m;
+    keep = (int32_t)k;
+    n_local = (int32_t)wl;
+    n_global = (int32_t)(k - wl);
+}
+
+}  // namespace swa

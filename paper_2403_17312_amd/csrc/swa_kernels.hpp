@@ -1,0 +1,32 @@
+// Host-side launch interface between the C-ABI entry points and the kernels.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "swa.h"
+#include "swa_device.hpp"
+
+namespace swa {
+
+// Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.
+int ensure_dynamic_lds(const void* kernel, size_t bytes);
+
+// Threads per workgroup of the decode kernel for this many (sequence, head) pairs.
+int decode_block_threads(int64_t pairs);
+
+int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stream);
+
+int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
+                  void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
+                  const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
+                  float* probs_dbg, void* workspace, hipStream_t stream);
+
+int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* score, int32_t* pos,
+                   const int32_t* kept_idx, const int32_t* kept_cnt, int32_t* cache_len,
+                   hipStream_t stream);
+
+int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
+                   const int32_t* cache_len, float* score, hipStream_t stream);
+
+}  // namespace swa

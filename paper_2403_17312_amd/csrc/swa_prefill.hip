@@ -1,0 +1,251 @@
+// Prefill importance seed on MFMA: the local attention sum of Algorithm 1 line 2
+// evaluated at the end of the prompt,
+//   score[j] = sum_{r<R} softmax_causal(Q_tail K^T * scale)[r, j].
+// One workgroup (4 waves) per (sequence, head) pair.  The R x s logit tile is
+// never stored: pass 1 computes every query row's max and normaliser, pass 2
+// recomputes the logits and reduces exp(z - max_r) / sum_r over the rows.
+//
+// MFMA operand layout used here (32x32 tiles, wave64): lane l supplies row
+// (l % 32) of its operand and the contiguous half-row (l / 32) of the head
+// dimension; successive MFMA issues walk along that half-row.  Both operands
+// use the same walk, so the contraction is over the whole head dimension
+// whatever order the hardware sums in.  The 32x32 fp32 result gives lane l
+// column (l % 32) and rows 8*(i/4) + 4*(l/32) + (i%4), i = 0..15.
+//   pass 1: A = key tile,   B = query tile -> lane owns ONE query, 16 keys
+//           (row statistics reduce inside the lane);
+//   pass 2: A = query tile, B = key tile   -> lane owns ONE key, 16 queries
+//           (column sums reduce inside the lane).
+#include "swa_kernels.hpp"
+
+namespace swa {
+
+struct PrefillArgs {
+    const char* q_tail;
+    const char* k_cache;
+    const int32_t* cache_len;
+    float* score;
+    int32_t h, cap, R;
+    float scale_log2e;
+};
+
+template <typename T>
+struct Mfma;
+template <>
+struct Mfma<F16> {
+    static constexpr int kElemsPerIssue = 8;
+    // one issue consumes a whole 16-byte vector
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mfma<BF16> {
+    static constexpr int kElemsPerIssue = 8;
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mfma<F32> {
+    static constexpr int kElemsPerIssue = 1;
+    // four issues per 16-byte vector, one fp32 element each
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.x), u2f(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.y), u2f(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.z), u2f(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.w), u2f(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
+// Merge two (max, sum-of-exp2) pairs of disjoint key sets.
+__device__ __forceinline__ void merge_stats(float& M, float& L, float M2, float L2)
+{
+    const float Mn = fmaxf(M, M2);
+    if (Mn == -INFINITY) return;   // both empty
+    const float a = (M == -INFINITY) ? 0.f : L * exp2f(M - Mn);
+    const float b = (M2 == -INFINITY) ? 0.f : L2 * exp2f(M2 - Mn);
+    M = Mn;
+    L = a + b;
+}
+
+template <typename T, int D, int RT>
+__global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
+{
+    constexpr int NT = 256;
+    constexpr int NW = NT / kWave;
+    constexpr int ROWB = D * Elem<T>::kBytes;
+    constexpr int NV = (ROWB / 2) / 16;   // 16-byte vectors per half-row
+    constexpr int RP = RT * 32;           // padded query rows
+
+    __shared__ float s_m[NW][RP];
+    __shared__ float s_l[NW][RP];
+    __shared__ float s_M[RP];
+    __shared__ float s_invL[RP];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int hb = lane >> 5;
+    const int64_t pair = blockIdx.x;
+    const int s = a.cache_len[pair / a.h];
+    const int R = a.R;
+    const int cap = a.cap;
+    float* Sp = a.score + pair * (int64_t)cap;
+
+    if (s <= 0) {
+        for (int j = tid; j < cap; j += NT) Sp[j] = 0.f;
+        return;
+    }
+
+    const char* Kp = a.k_cache + pair * (int64_t)cap * ROWB;
+    const char* Qp = a.q_tail + pair * (int64_t)R * ROWB;
+
+    // Query fragments stay in registers for both passes.  Rows >= R are zero.
+    Vec16 qv[RT][NV];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const int r = rt * 32 + l32;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) {
+            qv[rt][v] = (r < R) ? load16(Qp + (int64_t)r * ROWB + hb * (ROWB / 2) + v * 16)
+                                : Vec16{0u, 0u, 0u, 0u};
+        }
+    }
+
+    const int ntiles = (s + 31) / 32;
+    const int t_off = s - R;   // query r sits at position t_off + r and sees keys 0..t_off+r
+
+    // ------------------------------ pass 1: row statistics ------------------------------
+    float M[RT], L[RT];
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        M[rt] = -INFINITY;
+        L[rt] = 0.f;
+    }
+    for (int tile = wave; tile < ntiles; tile += NW) {
+        int krow = tile * 32 + l32;
+        krow = krow < s ? krow : s - 1;   // clamped rows are masked below
+        Vec16 kv[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) kv[v] = load16(Kp + (int64_t)krow * ROWB + hb * (ROWB / 2) + v * 16);
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float16_t c;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) c = Mfma<T>::run(kv[v], qv[rt][v], c);   // C[key][query]
+            const int r = rt * 32 + l32;
+            const int tmax = (r < R) ? t_off + r : -1;   // last visible key of this lane's query
+            float z[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = tile * 32 + 8 * (i / 4) + 4 * hb + (i % 4);
+                z[i] = (key <= tmax) ? c[i] * a.scale_log2e : -INFINITY;
+                mx = fmaxf(mx, z[i]);
+            }
+            if (mx > -INFINITY) {
+                const float Mn = fmaxf(M[rt], mx);
+                float acc = (M[rt] == -INFINITY) ? 0.f : L[rt] * exp2f(M[rt] - Mn);
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc += exp2f(z[i] - Mn);
+                M[rt] = Mn;
+                L[rt] = acc;
+            }
+        }
+    }
+#pragma unroll
+    for (int rt = 0; rt < RT; ++rt) {
+        const float M2 = __shfl_xor(M[rt], 32, kWave);
+        const float L2 = __shfl_xor(L[rt], 32, kWave);
+        merge_stats(M[rt], L[rt], M2, L2);
+        if (hb == 0) {
+            s_m[wave][rt * 32 + l32] = M[rt];
+            s_l[wave][rt * 32 + l32] = L[rt];
+        }
+    }
+    __syncthreads();
+    if (tid < RP) {
+        float Mt = s_m[0][tid], Lt = s_l[0][tid];
+#pragma unroll
+        for (int v = 1; v < NW; ++v) merge_stats(Mt, Lt, s_m[v][tid], s_l[v][tid]);
+        const bool ok = Mt > -INFINITY && Lt > 0.f;
+        s_M[tid] = ok ? Mt : 0.f;
+        s_invL[tid] = ok ? 1.f / Lt : 0.f;
+    }
+    __syncthreads();
+
+    // ------------------------------ pass 2: column sums ---------------------------------
+    for (int tile = wave; tile < ntiles; tile += NW) {
+        const int key = tile * 32 + l32;
+        const int krow = key < s ? key : s - 1;
+        Vec16 kv[NV];
+#pragma unroll
+        for (int v = 0; v < NV; ++v) kv[v] = load16(Kp + (int64_t)krow * ROWB + hb * (ROWB / 2) + v * 16);
+        float colsum = 0.f;
+#pragma unroll
+        for (int rt = 0; rt < RT; ++rt) {
+            float16_t c;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] = 0.f;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) c = Mfma<T>::run(qv[rt][v], kv[v], c);   // C[query][key]
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int r = rt * 32 + 8 * (i / 4) + 4 * hb + (i % 4);
+                const bool vis = (r < R) && (key <= t_off + r);
+                const float p = exp2f(c[i] * a.scale_log2e - s_M[r]) * s_invL[r];
+                colsum += vis ? p : 0.f;
+            }
+        }
+        colsum += __shfl_xor(colsum, 32, kWave);
+        if (hb == 0 && key < s) Sp[key] = colsum;
+    }
+    for (int j = s + tid; j < cap; j += NT) Sp[j] = 0.f;
+}
+
+template <typename T, int D>
+static int launch_prefill_t(const PrefillArgs& a, int64_t pairs, hipStream_t stream)
+{
+    const int rt = (a.R + 31) / 32;
+    switch (rt) {
+        case 1: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 1>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
+        case 2: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 2>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
+        case 3: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 3>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
+        case 4: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 4>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
+        default: return SWA_ERR_BAD_SHAPE;
+    }
+    return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
+}
+
+int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
+                   const int32_t* cache_len, float* score, hipStream_t stream)
+{
+    PrefillArgs a;
+    a.q_tail = static_cast<const char*>(q_tail);
+    a.k_cache = static_cast<const char*>(k_cache);
+    a.cache_len = cache_len;
+    a.score = score;
+    a.h = p.h;
+    a.cap = p.cap;
+    a.R = R;
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    const int64_t pairs = (int64_t)p.b * p.h;
+    if (p.dtype == SWA_F32) {
+        return p.d == 64 ? launch_prefill_t<F32, 64>(a, pairs, stream) : launch_prefill_t<F32, 128>(a, pairs, stream);
+    } else if (p.dtype == SWA_F16) {
+        return p.d == 64 ? launch_prefill_t<F16, 64>(a, pairs, stream) : launch_prefill_t<F16, 128>(a, pairs, stream);
+    } else {
+        return p.d == 64 ? launch_prefill_t<BF16, 64>(a, pairs, stream) : launch_prefill_t<BF16, 128>(a, pairs, stream);
+    }
+}
+
+}  // namespace swa

@@ -1,0 +1,191 @@
+"""Lock-step parity harness: HIP path vs the fp64 oracle, with state adoption.
+
+Selection is discontinuous: an fp32 GPU and an independent fp64 oracle order
+near-tied importance scores differently, and one flipped eviction changes the
+cache for good.  So before every step the oracle's importance vector is
+overwritten with the GPU's fp32 values of the previous step (K, V, pos and the
+lengths are identical by construction: compaction is a pure copy and is itself
+checked bit-exactly).  Per step, on the sampled (sequence, head) pairs:
+  (i)   attention weights and new importance, GPU vs oracle from the adopted
+        state: |delta| <= 1e-5 * |oracle| (+ 1e-12);
+  (ii)  kept indices: the oracle's selection routine applied to the GPU's own
+        fp32 importance values must equal kept_idx / kept_cnt bit-exactly; the
+        oracle's selection from its fp64 values may differ only in tokens whose
+        fp64 importance is within 2e-5 relative of the cutoff (counted);
+  (iii) output vs the oracle's sparse attention over that kept set:
+        max |delta| <= atol and per-pair relative L2 error <= rtol
+        (fp16/bf16: 2e-3 and 1e-2; fp32: 2e-5 and 1e-4);
+  (iv)  after compaction: K, V, importance, pos, cache_len equal the oracle's
+        stable gather bit-exactly.
+"""
+from __future__ import annotations
+
+import dataclasses
+from typing import List, Optional, Sequence
+
+import numpy as np
+import torch
+
+from oracle import swa_oracle as O
+from paper_2403_17312_amd import binding as B
+from paper_2403_17312_amd import workload as W
+
+TOL = {"f16": (2e-3, 1e-2), "bf16": (2e-3, 1e-2), "f32": (2e-5, 1e-4)}
+
+
+@dataclasses.dataclass
+class Report:
+    steps: int = 0
+    pairs: int = 0
+    max_prob_rel: float = 0.0
+    max_score_rel: float = 0.0
+    max_out_abs: float = 0.0
+    max_out_rel: float = 0.0
+    near_tie_flips: int = 0
+    evictions: int = 0
+    moved_rows: int = 0
+
+
+def _np64(t: torch.Tensor) -> np.ndarray:
+    return t.detach().to("cpu").to(torch.float64).numpy().copy()
+
+
+def _sub(t: torch.Tensor, seqs, heads) -> torch.Tensor:
+    return t[seqs][:, heads]
+
+
+def new_state(wl: W.Workload, prompt: dict, debug_probs: bool = True) -> B.DecodeState:
+    params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+    st = B.DecodeState(params, device=prompt["K"].device, debug_probs=debug_probs)
+    st.K, st.V, st.pos = prompt["K"], prompt["V"], prompt["pos"]
+    st.cache_len.copy_(prompt["cache_len"])
+    st.seq_len.copy_(prompt["cache_len"])
+    return st
+
+
+def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
+    atol, rtol = TOL[dtype]
+    err = np.abs(out_gpu - out_ref)
+    assert np.all(np.isfinite(out_gpu)), what
+    rel = np.linalg.norm(out_gpu - out_ref, axis=-1) / np.maximum(np.linalg.norm(out_ref, axis=-1), 1e-30)
+    assert err.max() <= atol, f"{what}: max abs {err.max():.3e} > {atol}"
+    assert rel.max() <= rtol, f"{what}: rel L2 {rel.max():.3e} > {rtol}"
+    return float(err.max()), float(rel.max())
+
+
+def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
+                 seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
+                 compact_every: int = 1, slack: str = "nan", check_steps=None,
+                 prompt: Optional[dict] = None, verbose: bool = False) -> Report:
+    """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
+    steps = wl.steps if steps is None else steps
+    seqs = list(range(wl.b)) if seqs is None else list(seqs)
+    heads = list(range(wl.h)) if heads is None else list(heads)
+    prompt = W.make_prompt(wl, device, slack=slack) if prompt is None else prompt
+    st = new_state(wl, prompt)
+    rep = Report(pairs=len(seqs) * len(heads))
+    seqs_t = torch.tensor(seqs, device=device)
+    heads_t = torch.tensor(heads, device=device)
+
+    # oracle-side state of the sampled pairs
+    K_o = _np64(_sub(st.K, seqs_t, heads_t))
+    V_o = _np64(_sub(st.V, seqs_t, heads_t))
+    pos_o = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
+    len_o = st.cache_len[seqs_t].cpu().numpy().copy()
+    n_o = len_o.copy()
+    score_o = np.zeros(K_o.shape[:3])
+
+    if wl.prefill_R > 0:
+        q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R)
+        st.prefill_scores(q_tail)
+        S_ref = O.prefill_scores(_np64(_sub(q_tail, seqs_t, heads_t)), K_o, len_o, wl.scale)
+        S_gpu = _np64(_sub(st.score, seqs_t, heads_t))
+        np.testing.assert_allclose(S_gpu, S_ref, rtol=1e-5, atol=1e-12, err_msg="prefill seed")
+        for i, L in enumerate(len_o):
+            assert np.all(S_gpu[i, :, L:] == 0.0)
+        score_o = S_gpu.copy()                                   # adopt
+    else:
+        st.score.zero_()
+
+    for t in range(steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        n_o = n_o + 1
+        st.decode_step(q, kn, vn)
+        do_check = check_steps is None or t in check_steps
+        do_compact = compact_every > 0 and (t + 1) % compact_every == 0
+
+        # ---- oracle step from the adopted state ---------------------------------
+        q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
+        kept_o, cnt_o, out_o, p_o = O.decode_step(q_o, kn_o, vn_o, K_o, V_o, score_o, pos_o, len_o,
+                                                  n_o, wl.w, wl.sparsity_bp, wl.scale)
+        score_g = _np64(_sub(st.score, seqs_t, heads_t))
+        kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
+        cnt_g = st.kept_cnt[seqs_t].cpu().numpy()
+        assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o), f"step {t}: cache_len"
+        assert np.array_equal(cnt_g, cnt_o), f"step {t}: kept_cnt {cnt_g} vs {cnt_o}"
+
+        if do_check:
+            p_g = _np64(_sub(st.probs, seqs_t, heads_t))
+            out_g = _np64(_sub(st.out, seqs_t, heads_t))
+            for i, m in enumerate(len_o):
+                pe = np.abs(p_g[i, :, :m] - p_o[i, :, :m])
+                assert np.all(pe <= 1e-5 * np.abs(p_o[i, :, :m]) + 1e-12), \
+                    f"step {t} seq {seqs[i]}: probs rel err {np.max(pe / (p_o[i, :, :m] + 1e-300)):.3e}"
+                assert np.all(p_g[i, :, m:] == 0.0)
+                se = np.abs(score_g[i, :, :m] - score_o[i, :, :m])
+                assert np.all(se <= 1e-5 * np.abs(score_o[i, :, :m]) + 1e-12), \
+                    f"step {t} seq {seqs[i]}: score rel err"
+                rep.max_prob_rel = max(rep.max_prob_rel, float(np.max(pe / (np.abs(p_o[i, :, :m]) + 1e-30))))
+                rep.max_score_rel = max(rep.max_score_rel,
+                                        float(np.max(se / (np.abs(score_o[i, :, :m]) + 1e-30))))
+            # (ii) index sets: oracle selection on the GPU's own fp32 scores, bit-exact
+            kept_ref, cnt_ref = O.select(score_g, len_o, n_o, wl.w, wl.sparsity_bp)
+            assert np.array_equal(cnt_ref, cnt_g)
+            for i, c in enumerate(cnt_g):
+                assert np.array_equal(kept_g[i, :, :c], kept_ref[i, :, :c]), \
+                    f"step {t} seq {seqs[i]}: kept_idx differs from selection on the GPU's scores"
+                # near-tie certificate against the oracle's own fp64 selection
+                for hd in range(len(heads)):
+                    a, b_ = set(kept_g[i, hd, :c].tolist()), set(kept_o[i, hd, :c].tolist())
+                    diff = a ^ b_
+                    if diff:
+                        m = len_o[i]
+                        nl = min(wl.w, m)
+                        cand = np.sort(score_o[i, hd, :m - nl])[::-1]
+                        cutoff = cand[c - nl - 1]
+                        for j in diff:
+                            assert abs(score_o[i, hd, j] - cutoff) <= 2e-5 * abs(cutoff), \
+                                f"step {t}: flipped token {j} is not a near tie"
+                        rep.near_tie_flips += len(diff) // 2
+            # (iii) output on the GPU's kept set
+            out_ref = O.sparse_attention(q_o, K_o, V_o, kept_g, cnt_g, wl.scale)
+            ea, er = check_out(out_g, out_ref, wl.dtype, f"step {t} out")
+            rep.max_out_abs, rep.max_out_rel = max(rep.max_out_abs, ea), max(rep.max_out_rel, er)
+
+        # ---- adopt the GPU's importance values; compaction ----------------------------
+        score_o = score_g.copy()
+        for i, c in enumerate(cnt_g):
+            rep.evictions += (int(len_o[i]) - int(c)) * len(heads)
+        if do_compact:
+            for i, c in enumerate(cnt_g):
+                for hd in range(len(heads)):
+                    rep.moved_rows += int(np.sum(kept_g[i, hd, :c] != np.arange(c)))
+            st.compact()
+            O.compact(K_o, V_o, score_o, pos_o, kept_g, cnt_g, len_o)
+            assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o)
+            if do_check:
+                K_g = _np64(_sub(st.K, seqs_t, heads_t))
+                V_g = _np64(_sub(st.V, seqs_t, heads_t))
+                s_g = _np64(_sub(st.score, seqs_t, heads_t))
+                pos_g = _sub(st.pos, seqs_t, heads_t).cpu().numpy()
+                for i, L in enumerate(len_o):
+                    assert np.array_equal(K_g[i, :, :L], K_o[i, :, :L]), f"step {t}: K after compaction"
+                    assert np.array_equal(V_g[i, :, :L], V_o[i, :, :L]), f"step {t}: V after compaction"
+                    assert np.array_equal(s_g[i, :, :L], score_o[i, :, :L]), f"step {t}: score after compaction"
+                    assert np.array_equal(pos_g[i, :, :L], pos_o[i, :, :L]), f"step {t}: pos after compaction"
+        rep.steps += 1
+        if verbose and (t % 16 == 0 or t == steps - 1):
+            print(f"  [{wl.name}] step {t}: m={len_o.tolist()[:4]} ok", flush=True)
+    assert st.check_status() == 0
+    return rep

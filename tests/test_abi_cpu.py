@@ -1,0 +1,119 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every
+symbol the header declares, and rejects bad arguments before touching the device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2403_17312_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2403_17312_amd import build
+        build.build()
+    binding.lib()
+    return binding
+
+
+def _declared_functions():
+    text = open(os.path.join(ROOT, "include", "swa.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(swa_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol(B):
+    names = _declared_functions()
+    assert set(names) == set(B.EXPORTS), names
+    L = ctypes.CDLL(B.LIB_PATH)
+    for n in names:
+        assert hasattr(L, n), n
+
+
+def test_params_struct_matches_header(B):
+    text = open(os.path.join(ROOT, "include", "swa.h")).read()
+    body = re.search(r"typedef struct \{(.*?)\} swa_params;", text, flags=re.S).group(1)
+    body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
+    fields = re.findall(r"(int32_t|float)\s+(\w+);", body)
+    assert [f[1] for f in fields] == [f[0] for f in B.SwaParams._fields_]
+    assert ctypes.sizeof(B.SwaParams) == 32
+    assert int(re.search(r"#define SWA_MAX_CAP (\d+)", text).group(1)) == B.SWA_MAX_CAP
+    assert int(re.search(r"#define SWA_MAX_PREFILL_ROWS (\d+)", text).group(1)) == B.SWA_MAX_PREFILL_ROWS
+
+
+def test_strerror_covers_all_codes(B):
+    for code in range(0, -9, -1):
+        msg = B.strerror(code)
+        assert msg and "unknown" not in msg
+    assert "unknown" in B.strerror(-99)
+
+
+def test_budget_helper_matches_hand_worked_values(B):
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "keep_budget.txt"))
+            if l[0] != "#"]
+    for n, sp, _, keep in rows:
+        assert B.swa_budget(int(n), int(n), 1, int(sp) * 100)[0] == int(keep)
+    assert B.swa_budget(1000, 50, 8, 8000) == (50, 8, 42)
+    assert B.swa_budget(100, 5, 64, 9000) == (5, 5, 0)
+    with pytest.raises(B.SwaError):
+        B.swa_budget(10, 10, 1, 10000)
+
+
+def test_workspace_bytes(B):
+    p = B.make_params(16, 32, 128, 545, 16, 8000, B.SWA_F16)
+    n = B.swa_workspace_bytes(p)
+    assert n >= 64 + 4 * 16 and n % 256 == 0
+    assert B.swa_workspace_bytes(B.make_params(16, 32, 96, 545, 16, 8000, B.SWA_F16)) == 0
+
+
+@pytest.mark.parametrize("kw,code", [
+    (dict(d=96), "SWA_ERR_UNSUPPORTED_D"),
+    (dict(dtype=7), "SWA_ERR_UNSUPPORTED_DTYPE"),
+    (dict(b=0), "SWA_ERR_BAD_SHAPE"),
+    (dict(w=-1), "SWA_ERR_BAD_SHAPE"),
+    (dict(cap=0), "SWA_ERR_BAD_SHAPE"),
+    (dict(cap=12289), "SWA_ERR_CAPACITY"),
+    (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
+    (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
+    (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),
+])
+def test_bad_params_are_rejected_before_any_device_work(B, kw, code):
+    base = dict(b=2, h=2, d=64, cap=32, w=2, sparsity_bp=5000, dtype=B.SWA_F32, scale=0.0)
+    base.update(kw)
+    p = B.SwaParams(*[base[f[0]] for f in B.SwaParams._fields_])
+    L = B.lib()
+    fake = ctypes.c_void_p(0x1000)          # never dereferenced: validation fails first
+    want = getattr(B, code)
+    assert L.swa_decode_step(ctypes.byref(p), *([fake] * 15)) == want
+    assert L.swa_compact_kv(ctypes.byref(p), *([fake] * 9)) == want
+    assert L.swa_prefill_scores(ctypes.byref(p), fake, 4, fake, fake, fake, fake, fake) == want
+    assert L.swa_workspace_init(ctypes.byref(p), fake, fake) == want
+
+
+def test_null_and_misaligned_pointers_are_rejected(B):
+    p = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F32)
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    args = [ok] * 15
+    for i in [0, 1, 2, 3, 4, 5, 6, 7, 8, 9, 10, 11, 13]:      # every required pointer
+        a = list(args)
+        a[i] = None
+        assert L.swa_decode_step(ctypes.byref(p), *a) == B.SWA_ERR_NULL, i
+    a = list(args)
+    a[3] = ctypes.c_void_p(0x1008)
+    assert L.swa_decode_step(ctypes.byref(p), *a) == B.SWA_ERR_ALIGNMENT
+    assert L.swa_decode_step(None, *args) == B.SWA_ERR_NULL
+    assert L.swa_compact_kv(ctypes.byref(p), None, *([ok] * 8)) == B.SWA_ERR_NULL
+    assert L.swa_prefill_scores(ctypes.byref(p), ok, 0, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
+    assert L.swa_prefill_scores(ctypes.byref(p), ok, 129, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
+    assert L.swa_prefill_scores(ctypes.byref(p), None, 4, ok, ok, ok, ok, ok) == B.SWA_ERR_NULL
+
+
+def test_binding_fails_loudly_without_the_library(B, monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError, match="missing"):
+        B.lib()

@@ -1,0 +1,246 @@
+"""GPU parity tests: the HIP library (through its C ABI) against the fp64 oracle."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' on CPU-only hosts)")
+    from oracle import swa_oracle as O
+    from paper_2403_17312_amd import binding as B
+    from paper_2403_17312_amd import workload as W
+    import lockstep as LS
+    O.build()
+    B.lib()
+    return O, B, W, LS
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------
+# the five workloads, lock-step
+# ------------------------------------------------------------------------------------
+def test_c1_tiny_every_pair_every_step(env):
+    O, B, W, LS = env
+    _say("c1_tiny lockstep")
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"])
+    _say(f"  {rep}")
+    assert rep.steps == 16 and rep.evictions > 0
+
+
+def test_c1_tiny_with_prefill_seed_fp32_mfma(env):
+    O, B, W, LS = env
+    wl = W.CONFIGS["c1_tiny"].replace(prefill_R=8)
+    _say("c1_tiny lockstep with prefill seed (fp32 MFMA path)")
+    rep = LS.run_lockstep(wl)
+    _say(f"  {rep}")
+
+
+def test_c1_tiny_without_compaction(env):
+    # decode steps back to back with no compaction: every slot stays a candidate
+    O, B, W, LS = env
+    _say("c1_tiny lockstep, never compacted")
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"], compact_every=0)
+    assert rep.steps == 16
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"], compact_every=5)
+    assert rep.steps == 16
+
+
+def test_c2_opt6p7b_every_pair_every_step(env):
+    O, B, W, LS = env
+    _say("c2 lockstep")
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"])
+    _say(f"  {rep}")
+    assert rep.steps == 32
+
+
+def test_c3_opt13b_full_size_sampled_pairs(env):
+    O, B, W, LS = env
+    wl = W.CONFIGS["c3_opt13b"]
+    _say("c3 lockstep (full size on the GPU, sampled pairs checked)")
+    rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero")
+    _say(f"  {rep}")
+    assert rep.steps == 64
+
+
+def test_c4_opt30b_full_size_sampled_pairs_with_mfma_prefill(env):
+    O, B, W, LS = env
+    wl = W.CONFIGS["c4_opt30b"]
+    _say("c4 lockstep (full size, bf16, MFMA prefill seed)")
+    rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero")
+    _say(f"  {rep}")
+    assert rep.steps == 128
+
+
+@pytest.mark.parametrize("name", ["c5_llama7b_sp50", "c5_llama7b_sp80", "c5_llama7b_sp90"])
+def test_c5_llama7b_full_size_sampled_pairs(env, name):
+    O, B, W, LS = env
+    wl = W.CONFIGS[name]
+    lens = W.prompt_lengths(wl).tolist()
+    seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 0, 100, 255})
+    _say(f"{name} lockstep (full size, mixed lengths {min(lens)}..{max(lens)}, seqs {seqs})")
+    check = set(range(0, 256, 3)) | {1, 2, 254, 255}
+    rep = LS.run_lockstep(wl, seqs=seqs, heads=[0, 15, 31], slack="zero", check_steps=check)
+    _say(f"  {rep}")
+    assert rep.steps == 256
+    torch.cuda.empty_cache()
+
+
+# ------------------------------------------------------------------------------------
+# shapes, dtypes, edge cases
+# ------------------------------------------------------------------------------------
+@pytest.mark.parametrize("dtype", ["f32", "f16", "bf16"])
+@pytest.mark.parametrize("d", [64, 128])
+def test_every_dtype_and_head_dim(env, dtype, d):
+    O, B, W, LS = env
+    wl = W.Workload(f"t_{dtype}_{d}", 11, b=3, h=5, d=d, dtype=dtype, prompt_lo=40, prompt_hi=333,
+                    steps=12, w=7, sparsity_bp=7000, hh_frac=0.02, prefill_R=5)
+    _say(f"dtype {dtype} d {d}")
+    rep = LS.run_lockstep(wl)
+    assert rep.steps == 12 and rep.evictions > 0
+
+
+@pytest.mark.parametrize("w,sp,R", [(0, 5000, 1), (1, 9999, 33), (500, 8000, 64), (4, 0, 128),
+                                    (16, 9000, 97)])
+def test_window_and_sparsity_extremes(env, w, sp, R):
+    # w = 0 (no window), sparsity ~1 (only the window survives), w larger than the
+    # cache (nothing evicted), sparsity 0 (dense), prefill rows beyond the prompt start
+    O, B, W, LS = env
+    wl = W.Workload("t_ext", 12, b=4, h=3, d=128, dtype="f16", prompt_lo=1, prompt_hi=150,
+                    steps=10, w=w, sparsity_bp=sp, hh_frac=0.02, prefill_R=R)
+    _say(f"extremes w={w} sp={sp} R={R} lens={W.prompt_lengths(wl).tolist()}")
+    rep = LS.run_lockstep(wl)
+    assert rep.steps == 10
+
+
+def test_workgroup_size_variants_and_large_cap(env):
+    # pair counts that select the 1024-, 512- and 256-thread kernels; cap near the LDS limit
+    O, B, W, LS = env
+    for b, h, hi, steps in [(1, 2, 3000, 4), (8, 100, 300, 4), (16, 130, 200, 4)]:
+        wl = W.Workload("t_wg", 13, b=b, h=h, d=128, dtype="bf16", prompt_lo=hi // 2, prompt_hi=hi,
+                        steps=steps, w=9, sparsity_bp=8500, hh_frac=0.01)
+        _say(f"workgroup variant b={b} h={h}")
+        LS.run_lockstep(wl, seqs=list(range(min(b, 4))), heads=[0, h - 1])
+    wl = W.Workload("t_cap", 14, b=1, h=2, d=64, dtype="f16", prompt_lo=12000, prompt_hi=12000,
+                    steps=3, w=64, sparsity_bp=9000, hh_frac=0.001)
+    assert wl.cap <= B.SWA_MAX_CAP
+    _say("large cap")
+    LS.run_lockstep(wl)
+
+
+def test_exact_ties_go_to_the_lowest_slot(env):
+    # identical keys => identical logits => bitwise-equal probabilities and scores
+    O, B, W, LS = env
+    b, h, d, cap, L, w = 2, 3, 128, 700, 600, 5
+    params = B.make_params(b, h, d, cap, w, 6000, torch.float16)
+    st = B.DecodeState(params, debug_probs=True)
+    g = torch.Generator(device="cuda").manual_seed(5)
+    key = torch.randn((d,), generator=g, device="cuda").half()
+    st.K[:, :, :L] = key
+    st.V[:, :, :L] = torch.randn((b, h, L, d), generator=g, device="cuda").half()
+    st.cache_len.fill_(L)
+    st.seq_len.fill_(L + 1)
+    q = torch.randn((b, h, d), generator=g, device="cuda").half()
+    kn = key.expand(b, h, d).contiguous()
+    vn = torch.randn((b, h, d), generator=g, device="cuda").half()
+    st.decode_step(q, kn, vn)
+    keep, nl, ng = B.swa_budget(L + 1, L + 1, w, 6000)
+    assert st.kept_cnt.tolist() == [keep] * b
+    expect = list(range(ng)) + list(range(L + 1 - nl, L + 1))
+    kept = st.kept_idx.cpu().numpy()
+    for s in range(b):
+        for hd in range(h):
+            assert kept[s, hd, :keep].tolist() == expect
+    p = st.probs.cpu().numpy()
+    assert np.all(p[:, :, :L + 1] == p[:, :, :1])
+
+
+def test_capacity_overflow_is_reported_and_nothing_is_written(env):
+    O, B, W, LS = env
+    b, h, d, cap = 3, 2, 64, 16
+    params = B.make_params(b, h, d, cap, 2, 5000, torch.float32)
+    st = B.DecodeState(params)
+    st.K.normal_()
+    st.V.normal_()
+    st.cache_len.copy_(torch.tensor([5, 16, 15], dtype=torch.int32))   # sequence 1 is full
+    st.seq_len.copy_(torch.tensor([6, 17, 16], dtype=torch.int32))
+    K0, V0, s0 = st.K.clone(), st.V.clone(), st.score.clone()
+    st.kept_cnt.fill_(-7)
+    x = torch.randn((b, h, d), device="cuda")
+    st.decode_step(x, x, x)
+    assert st.check_status() == B.SWA_ERR_CAPACITY
+    assert st.check_status() == 0                       # sticky bit is cleared by the read
+    assert st.cache_len.tolist() == [6, 16, 16]
+    assert st.kept_cnt[1].item() == -7
+    assert torch.equal(st.K[1], K0[1]) and torch.equal(st.V[1], V0[1]) and torch.equal(st.score[1], s0[1])
+    # a second step: arrival counters were reset, sequence 2 is now full as well
+    st.seq_len += 1
+    st.decode_step(x, x, x)
+    assert st.cache_len.tolist() == [7, 16, 16]
+    assert st.check_status() == B.SWA_ERR_CAPACITY
+
+
+def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
+    O, B, W, LS = env
+    wl = W.Workload("t_det", 15, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=400,
+                    steps=6, w=8, sparsity_bp=8000, hh_frac=0.02, prefill_R=16)
+    results = []
+    for rep in range(2):
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        st = LS.new_state(wl, prompt, debug_probs=False)
+        st.score.fill_(float("nan"))                    # prefill must overwrite every slot
+        st.prefill_scores(W.make_q_tail(wl, prompt["mu"], wl.prefill_R))
+        outs = []
+        for t in range(wl.steps):
+            q, kn, vn = W.make_step(wl, t, prompt["mu"])
+            st.seq_len += 1
+            st.decode_step(q, kn, vn)
+            outs.append(st.out.clone())
+            st.compact()
+        lens = st.cache_len.tolist()
+        for s, L in enumerate(lens):
+            assert torch.isnan(st.K[s, :, wl.prompt_hi + wl.steps:]).all()   # beyond any append
+        assert not torch.isnan(torch.stack(outs)).any()
+        results.append((torch.stack(outs), st.score.clone(), st.kept_idx.clone(), st.K.clone(), lens))
+    a, b_ = results
+    assert torch.equal(a[0], b_[0]) and a[4] == b_[4]
+    for s, L in enumerate(a[4]):
+        assert torch.equal(a[1][s, :, :L], b_[1][s, :, :L])
+        assert torch.equal(a[2][s, :, :L], b_[2][s, :, :L])
+        assert torch.equal(a[3][s, :, :L], b_[3][s, :, :L])
+
+
+def test_prefill_scores_edge_shapes(env):
+    O, B, W, LS = env
+    for dtype, d in [("f16", 128), ("bf16", 64), ("f32", 128)]:
+        for R in [1, 31, 32, 64, 100, 128]:
+            wl = W.Workload("t_pf", 16, b=5, h=2, d=d, dtype=dtype, prompt_lo=1, prompt_hi=260,
+                            steps=1, w=4, sparsity_bp=5000, hh_frac=0.02)
+            prompt = W.make_prompt(wl, "cuda", slack="nan")
+            prompt["cache_len"][0] = 0                    # an empty cache
+            st = LS.new_state(wl, prompt)
+            st.score.fill_(float("nan"))
+            qt = W.make_q_tail(wl, prompt["mu"], R)
+            st.prefill_scores(qt)
+            lens = st.cache_len.cpu().numpy()
+            S_ref = O.prefill_scores(LS._np64(qt), np.nan_to_num(LS._np64(st.K)), lens, wl.scale)
+            S_gpu = LS._np64(st.score)
+            np.testing.assert_allclose(S_gpu, S_ref, rtol=1e-5, atol=1e-12,
+                                       err_msg=f"{dtype} d={d} R={R} lens={lens.tolist()}")
+            np.testing.assert_allclose(S_gpu.sum(-1)[1:], np.minimum(R, lens[1:])[:, None], rtol=1e-5)
+
+
+def test_full_size_sampled_single_step_matches_dense_definition(env):
+    # At the largest shape, one step with sparsity 0: every sampled output must equal
+    # plain dense attention (Eq. 1-2) computed by the oracle pair by pair.
+    O, B, W, LS = env
+    wl = W.CONFIGS["c5_llama7b_sp80"].replace(sparsity_bp=0, steps=1)
+    rep = LS.run_lockstep(wl, seqs=[3, 77, 200], heads=[1, 30], slack="zero")
+    assert rep.evictions == 0
+    torch.cuda.empty_cache()
