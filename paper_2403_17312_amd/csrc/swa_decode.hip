@@ -44,7 +44,6 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 {
     constexpr int EPV = Elem<T>::kPerVec;   // elements per 16-byte vector
     constexpr int LPR = D / EPV;            // lanes per row
-    constexpr int RPW = kWave / LPR;        // rows per wave per load
     constexpr int NW = NT / kWave;
     constexpr int NG = NT / LPR;            // row groups per workgroup
     constexpr int ROWB = D * Elem<T>::kBytes;
@@ -251,7 +250,8 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             for (int u = 0; u < U; ++u) {
                 const int j = j0 + u * NG + grp;
                 if (j < keep) {
-                    const int idx = s_kept[j];
+                    int idx = s_kept[j];
+                    idx = idx < 0 ? 0 : (idx > len ? len : idx);
                     pw[u] = s_p[idx];
                     const char* src = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
                     vv[u] = load16(src + sub * 16);

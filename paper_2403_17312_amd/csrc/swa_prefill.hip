@@ -94,9 +94,10 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     const int l32 = lane & 31;
     const int hb = lane >> 5;
     const int64_t pair = blockIdx.x;
-    const int s = a.cache_len[pair / a.h];
-    const int R = a.R;
     const int cap = a.cap;
+    const int R = a.R;
+    int s = a.cache_len[pair / a.h];
+    s = s > cap ? cap : s;
     float* Sp = a.score + pair * (int64_t)cap;
 
     if (s <= 0) {

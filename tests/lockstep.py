@@ -12,9 +12,11 @@ checked bit-exactly).  Per step, on the sampled (sequence, head) pairs:
         fp32 importance values must equal kept_idx / kept_cnt bit-exactly; the
         oracle's selection from its fp64 values may differ only in tokens whose
         fp64 importance is within 2e-5 relative of the cutoff (counted);
-  (iii) output vs the oracle's sparse attention over that kept set:
-        max |delta| <= atol and per-pair relative L2 error <= rtol
-        (fp16/bf16: 2e-3 and 1e-2; fp32: 2e-5 and 1e-4);
+  (iii) output vs the oracle's sparse attention over that kept set, elementwise
+        |delta| <= atol + rel_elem * |oracle| and per-pair relative L2 error <= rtol:
+        fp16 2e-3, 0, 1e-2 (the stated bar); fp32 2e-5, 0, 1e-4; bf16 5e-4, 2^-8,
+        1e-2 (the output is rounded once to bf16, whose half-ulp is up to 2^-8
+        relative, so a pure absolute bar of 2e-3 cannot hold for |out| > 0.5);
   (iv)  after compaction: K, V, importance, pos, cache_len equal the oracle's
         stable gather bit-exactly.
 """
@@ -30,7 +32,7 @@ from oracle import swa_oracle as O
 from paper_2403_17312_amd import binding as B
 from paper_2403_17312_amd import workload as W
 
-TOL = {"f16": (2e-3, 1e-2), "bf16": (2e-3, 1e-2), "f32": (2e-5, 1e-4)}
+TOL = {"f16": (2e-3, 0.0, 1e-2), "bf16": (5e-4, 2.0 ** -8, 1e-2), "f32": (2e-5, 0.0, 1e-4)}
 
 
 @dataclasses.dataclass
@@ -64,11 +66,12 @@ def new_state(wl: W.Workload, prompt: dict, debug_probs: bool = True) -> B.Decod
 
 
 def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
-    atol, rtol = TOL[dtype]
+    atol, rel_elem, rtol = TOL[dtype]
     err = np.abs(out_gpu - out_ref)
     assert np.all(np.isfinite(out_gpu)), what
     rel = np.linalg.norm(out_gpu - out_ref, axis=-1) / np.maximum(np.linalg.norm(out_ref, axis=-1), 1e-30)
-    assert err.max() <= atol, f"{what}: max abs {err.max():.3e} > {atol}"
+    excess = err - (atol + rel_elem * np.abs(out_ref))
+    assert excess.max() <= 0, f"{what}: max abs {err.max():.3e} exceeds {atol} + {rel_elem:.2e}*|ref|"
     assert rel.max() <= rtol, f"{what}: rel L2 {rel.max():.3e} > {rtol}"
     return float(err.max()), float(rel.max())
 

@@ -233,7 +233,8 @@ def test_prefill_scores_edge_shapes(env):
             S_gpu = LS._np64(st.score)
             np.testing.assert_allclose(S_gpu, S_ref, rtol=1e-5, atol=1e-12,
                                        err_msg=f"{dtype} d={d} R={R} lens={lens.tolist()}")
-            np.testing.assert_allclose(S_gpu.sum(-1)[1:], np.minimum(R, lens[1:])[:, None], rtol=1e-5)
+            want = np.broadcast_to(np.minimum(R, lens[1:])[:, None].astype(np.float64), (4, 2))
+            np.testing.assert_allclose(S_gpu.sum(-1)[1:], want, rtol=1e-5)
 
 
 def test_full_size_sampled_single_step_matches_dense_definition(env):
