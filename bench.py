@@ -1,0 +1,334 @@
+#!/usr/bin/env python3
+"""Benchmark of the SWA decode hot path on one MI355X.
+
+A "step" is one pass of the whole hot path over one batch: swa_decode_step
+(append, scores, softmax, importance accumulation, selection, sparse output)
+followed by swa_compact_kv, for all b*h (sequence, head) pairs of one layer.
+
+The timed region walks complete decode trajectories of the workload (first
+step right after the prompt, then the steady state with compaction every
+step).  To keep the data HBM-cold the way a multi-layer model does, R
+independent replicas of the layer state are stepped round-robin (replica = one
+layer's cache): step i works on replica i % R at trajectory step i // R.
+Inputs are resident in HBM before the timed region starts.
+
+Prints ONE JSON line (see README / DESIGN for the fields).
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import math
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+
+
+def simulate_lengths(B, wl, lens):
+    """Host-side replay of the budget: per step, cached length m and kept count per sequence."""
+    cur = list(lens)
+    ms, keeps = [], []
+    for t in range(wl.steps):
+        m_t, k_t = [], []
+        for s, L in enumerate(cur):
+            n = lens[s] + t + 1
+            m = L + 1
+            keep, _, _ = B.swa_budget(n, m, wl.w, wl.sparsity_bp)
+            m_t.append(m)
+            k_t.append(keep)
+            cur[s] = keep
+        ms.append(m_t)
+        keeps.append(k_t)
+    return ms, keeps
+
+
+class Replica:
+    """One layer's device state plus the per-step logical lengths."""
+
+    def __init__(self, B, W, wl, prompt, torch):
+        params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+        st = B.DecodeState(params, device="cuda", debug_probs=False)
+        st.K.copy_(prompt["K"])
+        st.V.copy_(prompt["V"])
+        st.pos.copy_(prompt["pos"])
+        st.cache_len.copy_(prompt["cache_len"])
+        self.st = st
+        base = prompt["cache_len"].to(torch.int32)
+        self.seq_lens = torch.stack([base + (t + 1) for t in range(wl.steps)]).contiguous()  # [T, b]
+
+    def step(self, B, t, q, kn, vn):
+        st = self.st
+        B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+                          self.seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+        B.swa_compact_kv(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
+                         st.cache_len, st.workspace)
+
+
+def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True, log=None):
+    dev = "cuda"
+    T = wl.steps
+    R = max(1, math.ceil(steps / T))
+    Rw = max(1, math.ceil(warmup / T)) if warmup > 0 else 0
+    prompt = W.make_prompt(wl, dev)
+    lens = prompt["lengths"]
+    inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(T)]
+    q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R) if wl.prefill_R > 0 else None
+    ms, keeps = simulate_lengths(B, wl, lens)
+
+    def fresh(n):
+        reps = [Replica(B, W, wl, prompt, torch) for _ in range(n)]
+        if q_tail is not None:
+            for r in reps:
+                r.st.prefill_scores(q_tail)
+        return reps
+
+    def run(reps, count):
+        n = len(reps)
+        for i in range(count):
+            t, r = divmod(i, n)
+            q, kn, vn = inputs[t]
+            reps[r].step(B, t, q, kn, vn)
+
+    # -------- warm-up on its own replicas (also raises the LDS limit before any capture)
+    if Rw:
+        wreps = fresh(Rw)
+        run(wreps, warmup)
+        torch.cuda.synchronize()
+        del wreps
+
+    # -------- prefill seed timing (separate from the decode metric)
+    prefill_ms = None
+    if q_tail is not None:
+        tmp = fresh(1)[0]
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        tmp.st.prefill_scores(q_tail)
+        e1.record()
+        torch.cuda.synchronize()
+        prefill_ms = e0.elapsed_time(e1)
+        del tmp
+
+    # -------- timed region: exactly `steps` steps
+    reps = fresh(R)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    if mode == "graph":
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            run(reps, steps)
+        torch.cuda.synchronize()
+        t_wall0 = time.perf_counter()
+        e0.record()
+        g.replay()
+        e1.record()
+        torch.cuda.synchronize()
+        t_wall1 = time.perf_counter()
+    else:
+        t_wall0 = time.perf_counter()
+        e0.record()
+        run(reps, steps)
+        e1.record()
+        torch.cuda.synchronize()
+        t_wall1 = time.perf_counter()
+    total_ms = e0.elapsed_time(e1)
+    wall_ms = (t_wall1 - t_wall0) * 1e3
+    for r in reps:
+        assert r.st.check_status() == 0
+    del reps
+
+    # -------- accounting
+    kv_tokens = 0
+    alg_bytes = 0
+    for i in range(steps):
+        t = i // R
+        kv_tokens += sum(ms[t])
+        for m, k in zip(ms[t], keeps[t]):
+            alg_bytes += wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+
+    res = {
+        "workload": wl.name, "steps": steps, "replicas": R, "mode": mode,
+        "ms_per_step": total_ms / steps, "total_ms": total_ms, "host_wall_ms": wall_ms,
+        "kv_tokens_per_s": kv_tokens / (total_ms * 1e-3),
+        "generated_tokens_per_s": wl.b * steps / (total_ms * 1e-3),
+        "alg_bytes_per_step": alg_bytes / steps,
+        "alg_gbs_whole_step": alg_bytes / (total_ms * 1e-3) / 1e9,
+        "prefill_seed_ms": prefill_ms,
+    }
+
+    # -------- per-kernel durations with HIP events on the launch stream (separate pass)
+    if want_kernel_times:
+        reps = fresh(R)
+        torch.cuda.synchronize()
+        # cost of an empty event pair, to be subtracted
+        pairs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(64)]
+        for a, b_ in pairs:
+            a.record()
+            b_.record()
+        torch.cuda.synchronize()
+        empty_ms = sorted(a.elapsed_time(b_) for a, b_ in pairs)[len(pairs) // 2]
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        n = len(reps)
+        for i in range(steps):
+            t, r = divmod(i, n)
+            q, kn, vn = inputs[t]
+            st = reps[r].st
+            ev[i][0].record()
+            B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+                              reps[r].seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+            ev[i][1].record()
+            B.swa_compact_kv(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
+                             st.cache_len, st.workspace)
+            ev[i][2].record()
+        torch.cuda.synchronize()
+        dec = [max(0.0, e[0].elapsed_time(e[1]) - empty_ms) for e in ev]
+        cmp_ = [max(0.0, e[1].elapsed_time(e[2]) - empty_ms) for e in ev]
+        res["decode_kernel_ms_avg"] = sum(dec) / steps
+        res["compact_kernel_ms_avg"] = sum(cmp_) / steps
+        res["event_pair_overhead_ms"] = empty_ms
+        first = [dec[i] for i in range(steps) if i // n == 0]
+        steady = [dec[i] for i in range(steps) if i // n > 0]
+        res["decode_first_step_ms"] = sum(first) / max(1, len(first))
+        res["decode_steady_ms"] = sum(steady) / max(1, len(steady)) if steady else None
+        first_bytes = sum(wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+                          for m, k in zip(ms[0], keeps[0]))
+        res["decode_first_step_gbs"] = first_bytes / (res["decode_first_step_ms"] * 1e-3) / 1e9
+        if steady:
+            sb = [sum(wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+                      for m, k in zip(ms[i // n], keeps[i // n])) for i in range(steps) if i // n > 0]
+            res["decode_steady_gbs"] = sum(sb) / (sum(steady) * 1e-3) / 1e9
+        del reps
+    torch.cuda.empty_cache()
+    return res
+
+
+def cpu_baseline(wl, W, torch, budget_s=12.0):
+    """The fp64 oracle, as it stands, timed on the host cores on a bounded sample."""
+    import numpy as np
+    from oracle import swa_oracle as O
+    O.build()
+    sub_b = min(wl.b, 16)
+    wls = wl.replace(b=sub_b)
+    prompt = W.make_prompt(wls, "cpu")
+    K = prompt["K"].double().numpy().copy()
+    V = prompt["V"].double().numpy().copy()
+    pos = prompt["pos"].numpy().copy()
+    cache_len = prompt["cache_len"].numpy().copy()
+    score = np.zeros(K.shape[:3])
+    seq_len = cache_len.copy()
+    max_steps = wl.steps
+    inputs = [[x.double().numpy() for x in W.make_step(wls, t, prompt["mu"])] for t in range(max_steps)]
+    kv_tokens, elapsed, done = 0, 0.0, 0
+    for t in range(max_steps):
+        q, kn, vn = inputs[t]
+        seq_len = seq_len + 1
+        t0 = time.perf_counter()
+        kept_idx, kept_cnt, out, _ = O.decode_step(q, kn, vn, K, V, score, pos, cache_len, seq_len,
+                                                   wl.w, wl.sparsity_bp, wl.scale, want_probs=False)
+        kv_tokens += int(cache_len.sum())
+        O.compact(K, V, score, pos, kept_idx, kept_cnt, cache_len)
+        elapsed += time.perf_counter() - t0
+        done += 1
+        if elapsed > budget_s:
+            break
+    return {
+        "value": kv_tokens / elapsed, "unit": "KV tokens/s", "cores": O.num_threads(), "kind": "oracle",
+        "sample": f"{done} of {wl.steps} decode steps (from the prompt on) of {sub_b} of {wl.b} "
+                  f"sequences x {wl.h} heads of {wl.name}, fp64, {elapsed:.2f} s",
+    }
+
+
+def load_traffic(name):
+    path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
+    if not os.path.exists(path):
+        return None
+    try:
+        return json.load(open(path)).get(name)
+    except Exception:
+        return None
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 16 trajectories' worth)")
+    ap.add_argument("--warmup", type=int, default=None)
+    ap.add_argument("--config", default="c2_opt6p7b")
+    ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--others", default="c3_opt13b,c4_opt30b,c5_llama7b_sp80",
+                    help="comma list of further workloads summarised in the same line ('' = none)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
+              "(the path shards over (sequence, head) pairs with no exchange, see DESIGN.md)",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2403_17312_amd import binding as B
+    from paper_2403_17312_amd import workload as W
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()
+    torch.cuda.set_device(0)
+
+    wl = W.CONFIGS[args.config]
+    steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
+    warmup = args.warmup if args.warmup is not None else wl.steps
+    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W)
+
+    dec_ms = res["decode_kernel_ms_avg"]
+    achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
+    line = {
+        "metric": "SWA decode-step KV tokens/s",
+        "value": res["kv_tokens_per_s"],
+        "unit": "KV tokens/s",
+        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "ms_per_step": res["ms_per_step"],
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": wl.dtype, "data": "synthetic",
+        "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
+                   "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
+                   "replicas": res["replicas"], "launch": args.mode,
+                   "step": "swa_decode_step + swa_compact_kv"},
+        "roofline": {
+            "bound": "hbm", "kernel": "swa_decode_kernel",
+            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": load_traffic(wl.name),
+            "alg_bytes_per_launch": res["alg_bytes_per_step"], "avg_launch_ms": dec_ms,
+            "first_step_gbs": res.get("decode_first_step_gbs"), "steady_gbs": res.get("decode_steady_gbs"),
+        },
+        "whole_step_alg_gbs": res["alg_gbs_whole_step"],
+        "generated_tokens_per_s": res["generated_tokens_per_s"],
+        "detail": {k: res[k] for k in ("decode_kernel_ms_avg", "compact_kernel_ms_avg", "decode_first_step_ms",
+                                       "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
+                                       "prefill_seed_ms")},
+    }
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, W, torch)
+
+    others = []
+    for name in [x for x in args.others.split(",") if x and x != args.config]:
+        o = W.CONFIGS[name]
+        k = o.steps * max(1, 256 // o.steps)
+        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W)
+        a = r["alg_bytes_per_step"] / (r["decode_kernel_ms_avg"] * 1e-3) / 1e9
+        others.append({"workload": name, "steps": k, "kv_tokens_per_s": r["kv_tokens_per_s"],
+                       "ms_per_step": r["ms_per_step"], "decode_kernel_ms_avg": r["decode_kernel_ms_avg"],
+                       "compact_kernel_ms_avg": r["compact_kernel_ms_avg"],
+                       "roofline_frac": a / HBM_PEAK_GBS, "first_step_gbs": r.get("decode_first_step_gbs"),
+                       "steady_gbs": r.get("decode_steady_gbs"), "whole_step_alg_gbs": r["alg_gbs_whole_step"],
+                       "prefill_seed_ms": r["prefill_seed_ms"]})
+    if others:
+        line["other_workloads"] = others
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
