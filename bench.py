@@ -51,7 +51,7 @@ def simulate_lengths(B, wl, lens):
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
-    def __init__(self, B, W, wl, prompt, torch):
+    def __init__(self, B, W, wl, prompt, torch, len_bounds):
         params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
         st.K.copy_(prompt["K"])
@@ -61,12 +61,15 @@ class Replica:
         self.st = st
         base = prompt["cache_len"].to(torch.int32)
         self.seq_lens = torch.stack([base + (t + 1) for t in range(wl.steps)]).contiguous()  # [T, b]
+        # per-step params: the host knows an upper bound on the cached length of every step
+        self.params = [B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype,
+                                     len_bound=lb) for lb in len_bounds]
 
     def step(self, B, t, q, kn, vn):
         st = self.st
-        B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+        B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
                           self.seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
-        B.swa_compact_kv(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
+        B.swa_compact_kv(self.params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
                          st.cache_len, st.workspace)
 
 
@@ -80,9 +83,10 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True,
     inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(T)]
     q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R) if wl.prefill_R > 0 else None
     ms, keeps = simulate_lengths(B, wl, lens)
+    len_bounds = [max(m_t) for m_t in ms]
 
     def fresh(n):
-        reps = [Replica(B, W, wl, prompt, torch) for _ in range(n)]
+        reps = [Replica(B, W, wl, prompt, torch, len_bounds) for _ in range(n)]
         if q_tail is not None:
             for r in reps:
                 r.st.prefill_scores(q_tail)
@@ -180,10 +184,10 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True,
             q, kn, vn = inputs[t]
             st = reps[r].st
             ev[i][0].record()
-            B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+            B.swa_decode_step(reps[r].params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
                               reps[r].seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
             ev[i][1].record()
-            B.swa_compact_kv(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
+            B.swa_compact_kv(reps[r].params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
                              st.cache_len, st.workspace)
             ev[i][2].record()
         torch.cuda.synchronize()

@@ -38,7 +38,7 @@
 extern "C" {
 #endif
 
-#define SWA_MAX_CAP 12288 /* slots per (sequence, head); bounded by LDS per workgroup */
+#define SWA_MAX_CAP 16384 /* slots per (sequence, head); bounded by LDS per workgroup */
 #define SWA_MAX_PREFILL_ROWS 128
 
 typedef enum { SWA_F32 = 0, SWA_F16 = 1, SWA_BF16 = 2 } swa_dtype;
@@ -64,6 +64,10 @@ typedef struct {
     int32_t sparsity_bp; /* KV sparsity in basis points, 0..9999; caching ratio r = 1 - sparsity */
     int32_t dtype;       /* swa_dtype of q, k_new, v_new, caches, out */
     float scale;         /* logit scale; 0 selects 1/sqrt(d) (Eq. 1) */
+    int32_t len_bound;   /* 0, or an upper bound on cache_len[s] + 1 over all sequences for this
+                            call: lets swa_decode_step size its LDS to the live cache instead of
+                            cap.  A sequence that exceeds it is skipped and reported exactly like
+                            a full cache (capacity status bit). */
 } swa_params;
 
 /* Message for a swa_status code (static storage, never NULL). */

@@ -20,7 +20,7 @@ SWA_F32, SWA_F16, SWA_BF16 = 0, 1, 2
 SWA_OK = 0
 SWA_ERR_NULL, SWA_ERR_BAD_SHAPE, SWA_ERR_UNSUPPORTED_D, SWA_ERR_UNSUPPORTED_DTYPE = -1, -2, -3, -4
 SWA_ERR_BAD_SPARSITY, SWA_ERR_CAPACITY, SWA_ERR_HIP, SWA_ERR_ALIGNMENT = -5, -6, -7, -8
-SWA_MAX_CAP = 12288
+SWA_MAX_CAP = 16384
 SWA_MAX_PREFILL_ROWS = 128
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
@@ -31,7 +31,8 @@ EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_che
 class SwaParams(ctypes.Structure):
     _fields_ = [("b", ctypes.c_int32), ("h", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("cap", ctypes.c_int32), ("w", ctypes.c_int32), ("sparsity_bp", ctypes.c_int32),
-                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float)]
+                ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
+                ("len_bound", ctypes.c_int32)]
 
 
 class SwaError(RuntimeError):
@@ -79,9 +80,9 @@ def strerror(code: int) -> str:
 
 
 def make_params(b: int, h: int, d: int, cap: int, w: int, sparsity_bp: int, dtype,
-                scale: float = 0.0) -> SwaParams:
+                scale: float = 0.0, len_bound: int = 0) -> SwaParams:
     code = DTYPE_CODE[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
-    return SwaParams(b, h, d, cap, w, sparsity_bp, code, scale)
+    return SwaParams(b, h, d, cap, w, sparsity_bp, code, scale, len_bound)
 
 
 def _ptr(t: Optional[torch.Tensor]):

@@ -59,6 +59,7 @@ static int validate(const swa_params* p)
     if (p->cap > SWA_MAX_CAP) return SWA_ERR_CAPACITY;
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
+    if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
     return SWA_OK;
 }
 

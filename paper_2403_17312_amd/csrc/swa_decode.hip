@@ -3,11 +3,27 @@
 // A workgroup walks the whole step for its pair without leaving the CU:
 //   append -> logits GEMV over the cached keys (Eq. 1) -> softmax -> importance
 //   accumulation (running local attention sum, Alg. 1 line 2) -> budget and
-//   radix-select of the globally dynamic tokens (Alg. 1 lines 1, 3-5) -> gathered
-//   weighted sum of the kept values, renormalised over the kept set (lines 6-8).
+//   selection of the globally dynamic tokens (Alg. 1 lines 1, 3-5) -> weighted sum
+//   of the kept values, renormalised over the kept set (lines 6-8).
 // Logits, probabilities, selection keys and the kept list live in LDS, so the
-// only HBM traffic is one read of the key rows, one read of the kept value rows,
-// one read+write of the importance vector and the index list.
+// only HBM traffic is one read of the key rows, one read of the value rows that
+// are needed, one read+write of the importance vector and the index list.
+//
+// Two schedules, chosen per sequence from the number of evictions E = m - keep
+// (known before any data is read):
+//   * few evictions (the steady state under per-step compaction, E <= 1): ONE
+//     streaming pass loads key and value rows together and keeps flash-style
+//     running (max, sum, weighted-value) accumulators over ALL slots; after the
+//     selection, the evicted rows' contribution is subtracted:
+//         out = (dense - sum_E p_j v_j) / (1 - sum_E p_j).
+//     If the kept mass 1 - sum_E p_j is small the subtraction would cancel, and
+//     the kernel falls back to the gathered pass below.
+//   * many evictions (first step after a prompt, lazy compaction): the key pass
+//     runs alone, then only the kept value rows are gathered.
+// Selection: E == 0 keeps everything; E == 1 is a workgroup arg-min; otherwise an
+// LDS radix select (4 x 8 bits, most significant first) finds the n_global-th
+// largest key, and an ordered ballot/popcount compaction writes the ascending
+// kept list with ties resolved towards the lowest slot.
 #include "swa_kernels.hpp"
 
 namespace swa {
@@ -28,15 +44,34 @@ struct DecodeArgs {
     float* probs_dbg;
     int32_t* status;
     int32_t* arrive;
-    int32_t h, cap, cap_pad, w, sparsity_bp;
+    int32_t h, cap, lds_slots, w, sparsity_bp;
     float scale;
 };
+
+constexpr int kMaxFix = 8;           // evicted rows the subtractive schedule handles
+constexpr float kMinKeptMass = 0.05f;
+constexpr float kLog2e = 1.44269504088896340736f;
 
 // Monotone map fp32 -> uint32 (larger float <=> larger key).
 __device__ __forceinline__ uint32_t order_key(float f)
 {
     uint32_t u = f2u(f);
     return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Merge the flash accumulators (M, S, acc) of two disjoint row sets.
+template <int EPV>
+__device__ __forceinline__ void merge_acc(float& M, float& S, float* acc, float M2, float S2, const float* acc2)
+{
+    const float Mn = fmaxf(M, M2);
+    const float r1 = (M == -INFINITY) ? 0.f : fast_exp2((M - Mn) * kLog2e);
+    const float r2 = (M2 == -INFINITY) ? 0.f : fast_exp2((M2 - Mn) * kLog2e);
+    S = S * r1 + S2 * r2;
+#pragma unroll
+    for (int e = 0; e < EPV; ++e) acc[e] = acc[e] * r1 + acc2[e] * r2;
+    M = Mn;
 }
 
 template <typename T, int D, int NT>
@@ -47,18 +82,29 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     constexpr int NW = NT / kWave;
     constexpr int NG = NT / LPR;            // row groups per workgroup
     constexpr int ROWB = D * Elem<T>::kBytes;
-    constexpr int U = 4;                    // independent 16-byte loads in flight per lane
+    constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
+    constexpr int UF = 4;                   // key+value row pairs in flight per group (fused pass)
+    constexpr int UV = 4;                   // value rows in flight per group (gathered pass)
+    constexpr int SPF = 4;                  // importance values prefetched per thread
 
     extern __shared__ __align__(16) char smem[];
     float* s_p = reinterpret_cast<float*>(smem);                       // logits -> probabilities
-    uint32_t* s_key = reinterpret_cast<uint32_t*>(s_p + a.cap_pad);    // selection keys
-    int32_t* s_kept = reinterpret_cast<int32_t*>(s_key + a.cap_pad);   // ascending kept list
-    __shared__ float s_red[16];
+    uint32_t* s_key = reinterpret_cast<uint32_t*>(s_p + a.lds_slots);  // selection keys
+    // The ascending kept list (16-bit slots) overlays the key array: entry j is written
+    // only after key j' >= j of the same or a later tile has been read (see the ordered
+    // compaction below), and the keys are dead once the list is complete.
+    uint16_t* s_kept = reinterpret_cast<uint16_t*>(s_key);
+    __shared__ float s_redA[16];
+    __shared__ float s_redB[16];
+    __shared__ unsigned long long s_red64[16];
     __shared__ int32_t s_hist[256];
     __shared__ int32_t s_wcnt[2][16];
     __shared__ int32_t s_sel[2];
     __shared__ float s_acc[NW * D];
-    __shared__ float s_ps[16];
+    __shared__ float s_wS[16];
+    __shared__ float s_fix[kMaxFix * D];
+    __shared__ int32_t s_evict[kMaxFix];
+    __shared__ int32_t s_ecnt;
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -71,7 +117,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     const int len = a.cache_len[s];
     const int n = a.seq_len[s];
     const int m = len + 1;
-    const bool overflow = (m > a.cap) || (len < 0);
+    const bool overflow = (m > a.cap) || (m > a.lds_slots) || (len < 0);
 
     int keep = 0, n_local = 0, n_global = 0;
 
@@ -83,6 +129,19 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         const char* knew = a.k_new + pair * ROWB;
         const char* vnew = a.v_new + pair * ROWB;
 
+        budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global);
+        const int ncand = m - n_local;
+        const int E = m - keep;                       // evictions of this step
+        const bool fused = (E <= kMaxFix) && (8 * E <= m);
+
+        // ---- importance prefetch: the old values are needed only after the softmax ----
+        float sold[SPF];
+#pragma unroll
+        for (int k = 0; k < SPF; ++k) {
+            const int i = tid + k * NT;
+            sold[k] = (i < len) ? Sp[i] : 0.f;
+        }
+
         // ---- append ---------------------------------------------------------------
         if (tid < LPR) {
             store16(Kp + (int64_t)len * ROWB + tid * 16, load16(knew + tid * 16));
@@ -92,66 +151,197 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         } else if (tid == 2 * LPR) {
             a.pos[pair * (int64_t)cap + len] = n - 1;
         }
+        if (tid == 0) s_ecnt = 0;
 
-        // ---- logits: z_i = scale * q . k_i ------------------------------------------
         QFrag<T> qf;
         qf.load(load16(a.q + pair * ROWB + sub * 16));
-        for (int base = 0; base < m; base += NG * U) {
-            Vec16 kv[U];
+
+        float Mg = -INFINITY;     // running max of this group's logits
+        float Sg = 0.f;           // fused pass: running sum of exp(z - Mg)
+        float acc[EPV];           // fused pass: running sum of exp(z - Mg) * v
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u * NG + grp;
-                if (row < m) {
-                    const char* src = (row == len) ? knew : Kp + (int64_t)row * ROWB;
-                    kv[u] = load16(src + sub * 16);
-                } else {
-                    kv[u] = Vec16{0u, 0u, 0u, 0u};
+        for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+
+        if (fused) {
+            // ---- one pass over key AND value rows, flash-style accumulators ---------
+            for (int base = 0; base < m; base += NG * UF) {
+                Vec16 kv[UF], vv[UF];
+#pragma unroll
+                for (int u = 0; u < UF; ++u) {
+                    const int row = base + u * NG + grp;
+                    if (row < m) {
+                        const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
+                        const char* vs = (row == len) ? vnew : Vp + (int64_t)row * ROWB;
+                        kv[u] = load16(ks + sub * 16);
+                        vv[u] = load16(vs + sub * 16);
+                    } else {
+                        kv[u] = Vec16{0u, 0u, 0u, 0u};
+                        vv[u] = Vec16{0u, 0u, 0u, 0u};
+                    }
+                }
+                float z[UF];
+                float mc = -INFINITY;
+#pragma unroll
+                for (int u = 0; u < UF; ++u) {
+                    const int row = base + u * NG + grp;
+                    float d = qf.dot(kv[u], 0.f);
+#pragma unroll
+                    for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, kWave);
+                    d *= a.scale;
+                    if (sub == 0 && row < m) s_p[row] = d;
+                    z[u] = (row < m) ? d : -INFINITY;
+                    mc = fmaxf(mc, z[u]);
+                }
+                if (mc > -INFINITY) {
+                    const float Mn = fmaxf(Mg, mc);
+                    const float r = fast_exp2((Mg - Mn) * kLog2e);   // 0 when Mg is -inf
+                    Sg *= r;
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) acc[e] *= r;
+#pragma unroll
+                    for (int u = 0; u < UF; ++u) {
+                        const float ew = fast_exp2((z[u] - Mn) * kLog2e);   // 0 for padding rows
+                        float f[EPV];
+                        unpack<T>(vv[u], f);
+                        Sg += ew;
+#pragma unroll
+                        for (int e = 0; e < EPV; ++e) acc[e] = __builtin_fmaf(ew, f[e], acc[e]);
+                    }
+                    Mg = Mn;
                 }
             }
+            // combine the row groups of a wave, then park the wave partials in LDS
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int row = base + u * NG + grp;
-                float z = qf.dot(kv[u], 0.f);
+            for (int o = LPR; o < kWave; o <<= 1) {
+                const float M2 = __shfl_xor(Mg, o, kWave);
+                const float S2 = __shfl_xor(Sg, o, kWave);
+                float acc2[EPV];
 #pragma unroll
-                for (int o = LPR / 2; o > 0; o >>= 1) z += __shfl_xor(z, o, kWave);
-                if (sub == 0 && row < m) s_p[row] = z * a.scale;
+                for (int e = 0; e < EPV; ++e) acc2[e] = __shfl_xor(acc[e], o, kWave);
+                merge_acc<EPV>(Mg, Sg, acc, M2, S2, acc2);
             }
+            if (lane < LPR) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) s_acc[wave * D + sub * EPV + e] = acc[e];
+            }
+            if (lane == 0) {
+                s_redA[wave] = Mg;
+                s_wS[wave] = Sg;
+            }
+        } else {
+            // ---- key-only pass -------------------------------------------------------
+            for (int base = 0; base < m; base += NG * UK) {
+                Vec16 kv[UK];
+#pragma unroll
+                for (int u = 0; u < UK; ++u) {
+                    const int row = base + u * NG + grp;
+                    if (row < m) {
+                        const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
+                        kv[u] = load16(ks + sub * 16);
+                    } else {
+                        kv[u] = Vec16{0u, 0u, 0u, 0u};
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UK; ++u) {
+                    const int row = base + u * NG + grp;
+                    float d = qf.dot(kv[u], 0.f);
+#pragma unroll
+                    for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, kWave);
+                    d *= a.scale;
+                    if (row < m) {
+                        if (sub == 0) s_p[row] = d;
+                        Mg = fmaxf(Mg, d);
+                    }
+                }
+            }
+            Mg = wave_max(Mg);
+            if (lane == 0) s_redA[wave] = Mg;
         }
         __syncthreads();
 
-        // ---- softmax over the m cached slots ----------------------------------------
-        float mx = -INFINITY;
-        for (int i = tid; i < m; i += NT) mx = fmaxf(mx, s_p[i]);
-        mx = block_max<NT>(mx, s_red);
+        // ---- softmax over the m cached slots ------------------------------------------
+        float mx = s_redA[0];
+#pragma unroll
+        for (int v = 1; v < NW; ++v) mx = fmaxf(mx, s_redA[v]);
         float sum = 0.f;
         for (int i = tid; i < m; i += NT) {
             const float e = expf(s_p[i] - mx);
             s_p[i] = e;
             sum += e;
         }
-        sum = block_sum<NT>(sum, s_red);
+        sum = wave_sum(sum);
+        if (lane == 0) s_redB[wave] = sum;
+        __syncthreads();
+        sum = 0.f;
+#pragma unroll
+        for (int v = 0; v < NW; ++v) sum += s_redB[v];
 
-        // ---- importance accumulation --------------------------------------------------
-        for (int i = tid; i < m; i += NT) {
+        // ---- importance accumulation; arg-min bookkeeping for the E == 1 case ------------
+        unsigned long long best = ~0ull;   // (key << 32 | ~slot): min = lowest score, highest slot
+#pragma unroll
+        for (int k = 0; k < SPF; ++k) {
+            const int i = tid + k * NT;
+            if (i < m) {
+                const float p = s_p[i] / sum;
+                s_p[i] = p;
+                const float sc = sold[k] + p;
+                Sp[i] = sc;
+                const uint32_t key = order_key(sc);
+                s_key[i] = key;
+                if (i < ncand) {
+                    const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)i);
+                    best = c < best ? c : best;
+                }
+            }
+        }
+        for (int i = tid + SPF * NT; i < m; i += NT) {
             const float p = s_p[i] / sum;
             s_p[i] = p;
             const float old = (i == len) ? 0.f : Sp[i];
             const float sc = old + p;
             Sp[i] = sc;
-            s_key[i] = order_key(sc);
+            const uint32_t key = order_key(sc);
+            s_key[i] = key;
+            if (i < ncand) {
+                const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)i);
+                best = c < best ? c : best;
+            }
         }
         if (a.probs_dbg) {
+            __syncthreads();
             float* dbg = a.probs_dbg + pair * (int64_t)cap;
             for (int i = tid; i < cap; i += NT) dbg[i] = (i < m) ? s_p[i] : 0.f;
         }
 
-        // ---- budget + selection -------------------------------------------------------
-        budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global);
-        const int ncand = m - n_local;
-        __syncthreads();
-        if (n_global >= ncand) {
-            for (int i = tid; i < m; i += NT) s_kept[i] = i;   // nothing evicted
+        // ---- selection ---------------------------------------------------------------------
+        int32_t* kout = a.kept_idx + pair * (int64_t)cap;
+        bool have_list = false;           // s_kept holds the kept list
+        if (E == 0) {
+            for (int i = tid; i < m; i += NT) kout[i] = i;
+            __syncthreads();
+        } else if (E == 1 && n_global > 0) {
+            // evict the single candidate that loses: lowest score, ties -> highest slot
+#pragma unroll
+            for (int o = 32; o > 0; o >>= 1) {
+                const unsigned long long t = __shfl_xor(best, o, kWave);
+                best = t < best ? t : best;
+            }
+            if (lane == 0) s_red64[wave] = best;
+            __syncthreads();
+            best = s_red64[0];
+#pragma unroll
+            for (int v = 1; v < NW; ++v) best = s_red64[v] < best ? s_red64[v] : best;
+            const int jstar = (int)(~(uint32_t)(best & 0xffffffffull));
+            for (int j = tid; j < keep; j += NT) kout[j] = j + (j >= jstar ? 1 : 0);
+            if (tid == 0) {
+                s_evict[0] = jstar;
+                s_ecnt = 1;
+            }
+            __syncthreads();
         } else {
+            have_list = true;
+            __syncthreads();   // keys of every thread are in LDS
             // radix select: the n_global-th largest key among candidates 0..ncand-1
             uint32_t prefix = 0u, mask = 0u;
             int rem = n_global;
@@ -224,87 +414,140 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     if (v < wave) out_pos += c;
                     k_all += c;
                 }
-                if (kept) s_kept[out_pos] = i;
+                if (kept) s_kept[out_pos] = (uint16_t)i;
+                if (fused && i < m && !kept) {
+                    const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
+                    if (e < kMaxFix) s_evict[e] = i;
+                }
                 run_eq += eq_all;
                 run_out += k_all;
                 __syncthreads();
             }
-        }
-        __syncthreads();
-
-        // ---- kept list to HBM -----------------------------------------------------------
-        {
-            int32_t* kout = a.kept_idx + pair * (int64_t)cap;
             for (int j = tid; j < keep; j += NT) kout[j] = s_kept[j];
         }
 
-        // ---- sparse attention output: sum_kept p_i v_i / sum_kept p_i ---------------------
-        float acc[EPV];
+        // ---- output ---------------------------------------------------------------------------
+        // kept mass 1 - sum_E p_j decides whether the subtractive form is safe
+        bool subtract = fused;
+        float pe = 0.f;
+        int ec = 0;
+        if (fused) {
+            ec = s_ecnt;
+            ec = ec > kMaxFix ? kMaxFix : ec;
 #pragma unroll
-        for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
-        float ps = 0.f;
-        for (int j0 = 0; j0 < keep; j0 += NG * U) {
-            Vec16 vv[U];
-            float pw[U];
+            for (int k = 0; k < kMaxFix; ++k)
+                if (k < ec) pe += s_p[s_evict[k]];
+            subtract = (1.f - pe) >= kMinKeptMass;
+        }
+
+        if (subtract) {
+            // out = (dense - sum_E p_j v_j) / (1 - sum_E p_j)
+            if (grp < ec) {
+                int idx = s_evict[grp];
+                idx = idx < 0 ? 0 : (idx > len ? len : idx);
+                const float pw = s_p[idx];
+                const char* vs = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
+                float f[EPV];
+                unpack<T>(load16(vs + sub * 16), f);
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int j = j0 + u * NG + grp;
-                if (j < keep) {
-                    int idx = s_kept[j];
-                    idx = idx < 0 ? 0 : (idx > len ? len : idx);
-                    pw[u] = s_p[idx];
-                    const char* src = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
-                    vv[u] = load16(src + sub * 16);
-                } else {
-                    pw[u] = 0.f;
-                    vv[u] = Vec16{0u, 0u, 0u, 0u};
+                for (int e = 0; e < EPV; ++e) s_fix[grp * D + sub * EPV + e] = pw * f[e];
+            }
+            __syncthreads();
+            if (tid < LPR) {
+                float Mt = s_redA[0], St = s_wS[0];
+                float at[EPV];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) at[e] = s_acc[tid * EPV + e];
+                for (int v = 1; v < NW; ++v) {
+                    float a2[EPV];
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) a2[e] = s_acc[v * D + tid * EPV + e];
+                    merge_acc<EPV>(Mt, St, at, s_redA[v], s_wS[v], a2);
+                }
+                float f[EPV];
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) {
+                    float t = at[e] / St;
+                    for (int k = 0; k < ec; ++k) t -= s_fix[k * D + tid * EPV + e];
+                    f[e] = t / (1.f - pe);
+                }
+                store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
+            }
+        } else {
+            // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i
+            if (!have_list) {
+                // the E <= 1 paths wrote the list straight to HBM; rebuild it in LDS
+                const int jstar = (E == 1 && n_global > 0) ? s_evict[0] : m;
+                for (int j = tid; j < keep; j += NT) s_kept[j] = (uint16_t)(j + (j >= jstar ? 1 : 0));
+            }
+            __syncthreads();
+#pragma unroll
+            for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+            float ps = 0.f;
+            for (int j0 = 0; j0 < keep; j0 += NG * UV) {
+                Vec16 vv[UV];
+                float pw[UV];
+#pragma unroll
+                for (int u = 0; u < UV; ++u) {
+                    const int j = j0 + u * NG + grp;
+                    if (j < keep) {
+                        int idx = s_kept[j];
+                        idx = idx < 0 ? 0 : (idx > len ? len : idx);
+                        pw[u] = s_p[idx];
+                        const char* src = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
+                        vv[u] = load16(src + sub * 16);
+                    } else {
+                        pw[u] = 0.f;
+                        vv[u] = Vec16{0u, 0u, 0u, 0u};
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < UV; ++u) {
+                    float f[EPV];
+                    unpack<T>(vv[u], f);
+#pragma unroll
+                    for (int e = 0; e < EPV; ++e) acc[e] = __builtin_fmaf(pw[u], f[e], acc[e]);
+                    ps += pw[u];
                 }
             }
 #pragma unroll
-            for (int u = 0; u < U; ++u) {
+            for (int o = LPR; o < kWave; o <<= 1) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
+                ps += __shfl_xor(ps, o, kWave);
+            }
+            if (lane < LPR) {
+#pragma unroll
+                for (int e = 0; e < EPV; ++e) s_acc[wave * D + sub * EPV + e] = acc[e];
+                if (lane == 0) s_wS[wave] = ps;
+            }
+            __syncthreads();
+            if (tid < LPR) {
+                float pst = 0.f;
+#pragma unroll
+                for (int v = 0; v < NW; ++v) pst += s_wS[v];
                 float f[EPV];
-                unpack<T>(vv[u], f);
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) acc[e] = __builtin_fmaf(pw[u], f[e], acc[e]);
-                ps += pw[u];
+                for (int e = 0; e < EPV; ++e) {
+                    float t = 0.f;
+#pragma unroll
+                    for (int v = 0; v < NW; ++v) t += s_acc[v * D + tid * EPV + e];
+                    f[e] = t / pst;
+                }
+                store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
             }
-        }
-#pragma unroll
-        for (int o = LPR; o < kWave; o <<= 1) {
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) acc[e] += __shfl_xor(acc[e], o, kWave);
-            ps += __shfl_xor(ps, o, kWave);
-        }
-        if (lane < LPR) {
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) s_acc[wave * D + sub * EPV + e] = acc[e];
-            if (lane == 0) s_ps[wave] = ps;
-        }
-        __syncthreads();
-        if (tid < LPR) {
-            float pst = 0.f;
-#pragma unroll
-            for (int v = 0; v < NW; ++v) pst += s_ps[v];
-            float f[EPV];
-#pragma unroll
-            for (int e = 0; e < EPV; ++e) {
-                float t = 0.f;
-#pragma unroll
-                for (int v = 0; v < NW; ++v) t += s_acc[v * D + tid * EPV + e];
-                f[e] = t / pst;
-            }
-            store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
         }
     }
 
     // ---- per-sequence arrival: the last head to finish publishes the new length --------
+    // Every workgroup read cache_len[s] before it arrives here, and the publishing
+    // store is issued only after the atomic has returned, so no reader can see it.
     if (tid == 0) {
         if (overflow) {
             atomicOr(a.status, kStatusCapacityBit);
         } else {
             a.kept_cnt[s] = keep;
         }
-        __threadfence();
         const int old = atomicAdd(&a.arrive[s], 1);
         if (old == a.h - 1) {
             atomicExch(&a.arrive[s], 0);
@@ -356,14 +599,14 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.arrive = reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + kWsArriveOffset);
     a.h = p.h;
     a.cap = p.cap;
-    a.cap_pad = (p.cap + 63) & ~63;
+    const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
+    a.lds_slots = (bound + 63) & ~63;
     a.w = p.w;
     a.sparsity_bp = p.sparsity_bp;
     a.scale = scale;
 
     const int64_t pairs = (int64_t)p.b * p.h;
-    const size_t lds_bytes = (size_t)a.cap_pad * 12;
-    // Few pairs per CU: larger workgroups keep more loads in flight per CU.
+    const size_t lds_bytes = (size_t)a.lds_slots * 8;
     const int nt = decode_block_threads(pairs);
 
     if (p.dtype == SWA_F32) {

@@ -79,7 +79,8 @@ def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
 def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
-                 prompt: Optional[dict] = None, verbose: bool = False) -> Report:
+                 prompt: Optional[dict] = None, verbose: bool = False,
+                 use_len_bound: bool = False) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
@@ -110,11 +111,19 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
     else:
         st.score.zero_()
 
+    host_len = list(prompt["lengths"])          # host-side replay of every sequence's length
     for t in range(steps):
         q, kn, vn = W.make_step(wl, t, prompt["mu"])
         st.seq_len += 1
         n_o = n_o + 1
+        if use_len_bound:
+            # exact bound: the longest cache of this step, from the host's replay of the budget
+            st.params.len_bound = max(host_len) + 1
         st.decode_step(q, kn, vn)
+        for s_i in range(wl.b):
+            m_i = host_len[s_i] + 1
+            host_len[s_i] = (B.swa_budget(prompt["lengths"][s_i] + t + 1, m_i, wl.w, wl.sparsity_bp)[0]
+                             if compact_every > 0 and (t + 1) % compact_every == 0 else m_i)
         do_check = check_steps is None or t in check_steps
         do_compact = compact_every > 0 and (t + 1) % compact_every == 0
 

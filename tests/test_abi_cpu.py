@@ -39,7 +39,7 @@ def test_params_struct_matches_header(B):
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"(int32_t|float)\s+(\w+);", body)
     assert [f[1] for f in fields] == [f[0] for f in B.SwaParams._fields_]
-    assert ctypes.sizeof(B.SwaParams) == 32
+    assert ctypes.sizeof(B.SwaParams) == 36
     assert int(re.search(r"#define SWA_MAX_CAP (\d+)", text).group(1)) == B.SWA_MAX_CAP
     assert int(re.search(r"#define SWA_MAX_PREFILL_ROWS (\d+)", text).group(1)) == B.SWA_MAX_PREFILL_ROWS
 
@@ -75,13 +75,14 @@ def test_workspace_bytes(B):
     (dict(b=0), "SWA_ERR_BAD_SHAPE"),
     (dict(w=-1), "SWA_ERR_BAD_SHAPE"),
     (dict(cap=0), "SWA_ERR_BAD_SHAPE"),
-    (dict(cap=12289), "SWA_ERR_CAPACITY"),
+    (dict(cap=16385), "SWA_ERR_CAPACITY"),
+    (dict(len_bound=-1), "SWA_ERR_BAD_SHAPE"),
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
     (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),
 ])
 def test_bad_params_are_rejected_before_any_device_work(B, kw, code):
-    base = dict(b=2, h=2, d=64, cap=32, w=2, sparsity_bp=5000, dtype=B.SWA_F32, scale=0.0)
+    base = dict(b=2, h=2, d=64, cap=32, w=2, sparsity_bp=5000, dtype=B.SWA_F32, scale=0.0, len_bound=0)
     base.update(kw)
     p = B.SwaParams(*[base[f[0]] for f in B.SwaParams._fields_])
     L = B.lib()

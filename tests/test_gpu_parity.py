@@ -58,13 +58,17 @@ def test_c2_opt6p7b_every_pair_every_step(env):
     rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"])
     _say(f"  {rep}")
     assert rep.steps == 32
+    # the launch configuration bench.py times: LDS sized from the host's length bound
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], use_len_bound=True)
+    assert rep.steps == 32
 
 
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
     _say("c3 lockstep (full size on the GPU, sampled pairs checked)")
-    rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero")
+    rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero",
+                          use_len_bound=True)
     _say(f"  {rep}")
     assert rep.steps == 64
 
@@ -73,7 +77,7 @@ def test_c4_opt30b_full_size_sampled_pairs_with_mfma_prefill(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c4_opt30b"]
     _say("c4 lockstep (full size, bf16, MFMA prefill seed)")
-    rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero")
+    rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero", use_len_bound=True)
     _say(f"  {rep}")
     assert rep.steps == 128
 
@@ -86,7 +90,8 @@ def test_c5_llama7b_full_size_sampled_pairs(env, name):
     seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 0, 100, 255})
     _say(f"{name} lockstep (full size, mixed lengths {min(lens)}..{max(lens)}, seqs {seqs})")
     check = set(range(0, 256, 3)) | {1, 2, 254, 255}
-    rep = LS.run_lockstep(wl, seqs=seqs, heads=[0, 15, 31], slack="zero", check_steps=check)
+    rep = LS.run_lockstep(wl, seqs=seqs, heads=[0, 15, 31], slack="zero", check_steps=check,
+                          use_len_bound=True)
     _say(f"  {rep}")
     assert rep.steps == 256
     torch.cuda.empty_cache()
