@@ -3,6 +3,7 @@
 // swa_check_status) or reads device memory.
 #include <math.h>
 #include <stdio.h>
+#include <stdlib.h>
 
 #include <mutex>
 #include <unordered_map>
@@ -29,10 +30,15 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes)
 
 int decode_block_threads(int64_t pairs)
 {
-    // 256 CUs: with few pairs per CU a larger workgroup keeps more loads in flight.
-    if (pairs >= 256 * 8) return 256;
-    if (pairs >= 256 * 3) return 512;
-    return 1024;
+    // Tuning override (64, 128, 256 or 512), read once.
+    static const int forced = [] {
+        const char* e = getenv("SWA_DECODE_NT");
+        const int v = e ? atoi(e) : 0;
+        return (v == 64 || v == 128 || v == 256 || v == 512) ? v : 0;
+    }();
+    if (forced) return forced;
+    // Measured on MI355X: 256 threads once there are several pairs per CU, 128 below that.
+    return pairs >= 1024 ? 256 : 128;
 }
 
 __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)

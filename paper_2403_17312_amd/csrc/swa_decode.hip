@@ -83,7 +83,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     constexpr int NG = NT / LPR;            // row groups per workgroup
     constexpr int ROWB = D * Elem<T>::kBytes;
     constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
-    constexpr int UF = 4;                   // key+value row pairs in flight per group (fused pass)
+    constexpr int UF = 2;                   // key+value row pairs per group and pipeline stage (fused pass)
     constexpr int UV = 4;                   // value rows in flight per group (gathered pass)
     constexpr int SPF = 4;                  // importance values prefetched per thread
 
@@ -148,10 +148,11 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         } else if (tid < 2 * LPR) {
             const int t2 = tid - LPR;
             store16(Vp + (int64_t)len * ROWB + t2 * 16, load16(vnew + t2 * 16));
-        } else if (tid == 2 * LPR) {
-            a.pos[pair * (int64_t)cap + len] = n - 1;
         }
-        if (tid == 0) s_ecnt = 0;
+        if (tid == 0) {
+            a.pos[pair * (int64_t)cap + len] = n - 1;
+            s_ecnt = 0;
+        }
 
         QFrag<T> qf;
         qf.load(load16(a.q + pair * ROWB + sub * 16));
@@ -164,32 +165,35 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 
         if (fused) {
             // ---- one pass over key AND value rows, flash-style accumulators ---------
-            for (int base = 0; base < m; base += NG * UF) {
-                Vec16 kv[UF], vv[UF];
+            // Software-pipelined: the loads of stage i+1 are in flight while stage i is
+            // reduced, so the memory system never idles inside a wave.  Loads are
+            // unconditional (out-of-range rows re-read the newest row and get weight 0)
+            // so that the outstanding-load count is exact and stage i's wait does not
+            // also drain stage i+1.
+            constexpr int STEP = NG * UF;
+            auto load_stage = [&](int base, Vec16(&kv)[UF], Vec16(&vv)[UF]) {
 #pragma unroll
                 for (int u = 0; u < UF; ++u) {
-                    const int row = base + u * NG + grp;
-                    if (row < m) {
-                        const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
-                        const char* vs = (row == len) ? vnew : Vp + (int64_t)row * ROWB;
-                        kv[u] = load16(ks + sub * 16);
-                        vv[u] = load16(vs + sub * 16);
-                    } else {
-                        kv[u] = Vec16{0u, 0u, 0u, 0u};
-                        vv[u] = Vec16{0u, 0u, 0u, 0u};
-                    }
+                    int row = base + u * NG + grp;
+                    row = row < m ? row : len;
+                    const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
+                    const char* vs = (row == len) ? vnew : Vp + (int64_t)row * ROWB;
+                    kv[u] = load16(ks + sub * 16);
+                    vv[u] = load16(vs + sub * 16);
                 }
+            };
+            auto reduce_stage = [&](int base, const Vec16(&kv)[UF], const Vec16(&vv)[UF]) {
                 float z[UF];
+#pragma unroll
+                for (int u = 0; u < UF; ++u) z[u] = qf.dot(kv[u], 0.f);
+#pragma unroll
+                for (int u = 0; u < UF; ++u) z[u] = group_sum<LPR>(z[u]) * a.scale;
                 float mc = -INFINITY;
 #pragma unroll
                 for (int u = 0; u < UF; ++u) {
                     const int row = base + u * NG + grp;
-                    float d = qf.dot(kv[u], 0.f);
-#pragma unroll
-                    for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, kWave);
-                    d *= a.scale;
-                    if (sub == 0 && row < m) s_p[row] = d;
-                    z[u] = (row < m) ? d : -INFINITY;
+                    if (sub == 0 && row < m) s_p[row] = z[u];
+                    z[u] = (row < m) ? z[u] : -INFINITY;
                     mc = fmaxf(mc, z[u]);
                 }
                 if (mc > -INFINITY) {
@@ -209,6 +213,14 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     }
                     Mg = Mn;
                 }
+            };
+            Vec16 kA[UF], vA[UF], kB[UF], vB[UF];
+            load_stage(0, kA, vA);
+            for (int base = 0; base < m; base += 2 * STEP) {
+                load_stage(base + STEP, kB, vB);
+                reduce_stage(base, kA, vA);
+                load_stage(base + 2 * STEP, kA, vA);
+                reduce_stage(base + STEP, kB, vB);
             }
             // combine the row groups of a wave, then park the wave partials in LDS
 #pragma unroll
@@ -245,10 +257,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 #pragma unroll
                 for (int u = 0; u < UK; ++u) {
                     const int row = base + u * NG + grp;
-                    float d = qf.dot(kv[u], 0.f);
-#pragma unroll
-                    for (int o = LPR / 2; o > 0; o >>= 1) d += __shfl_xor(d, o, kWave);
-                    d *= a.scale;
+                    const float d = group_sum<LPR>(qf.dot(kv[u], 0.f)) * a.scale;
                     if (row < m) {
                         if (sub == 0) s_p[row] = d;
                         Mg = fmaxf(Mg, d);
@@ -347,7 +356,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             int rem = n_global;
             if (n_global > 0) {
                 for (int shift = 24; shift >= 0; shift -= 8) {
-                    if (tid < 256) s_hist[tid] = 0;
+                    for (int i = tid; i < 256; i += NT) s_hist[i] = 0;
                     __syncthreads();
                     for (int i = tid; i < ncand; i += NT) {
                         const uint32_t key = s_key[i];
@@ -442,15 +451,15 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 
         if (subtract) {
             // out = (dense - sum_E p_j v_j) / (1 - sum_E p_j)
-            if (grp < ec) {
-                int idx = s_evict[grp];
+            for (int k = grp; k < ec; k += NG) {
+                int idx = s_evict[k];
                 idx = idx < 0 ? 0 : (idx > len ? len : idx);
                 const float pw = s_p[idx];
                 const char* vs = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
                 float f[EPV];
                 unpack<T>(load16(vs + sub * 16), f);
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) s_fix[grp * D + sub * EPV + e] = pw * f[e];
+                for (int e = 0; e < EPV; ++e) s_fix[k * D + sub * EPV + e] = pw * f[e];
             }
             __syncthreads();
             if (tid < LPR) {
@@ -570,9 +579,10 @@ template <typename T, int D>
 static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, int nt, hipStream_t stream)
 {
     switch (nt) {
+        case 64: return launch_decode_nt<T, D, 64>(a, pairs, lds_bytes, stream);
+        case 128: return launch_decode_nt<T, D, 128>(a, pairs, lds_bytes, stream);
         case 256: return launch_decode_nt<T, D, 256>(a, pairs, lds_bytes, stream);
-        case 512: return launch_decode_nt<T, D, 512>(a, pairs, lds_bytes, stream);
-        default: return launch_decode_nt<T, D, 1024>(a, pairs, lds_bytes, stream);
+        default: return launch_decode_nt<T, D, 512>(a, pairs, lds_bytes, stream);
     }
 }
 

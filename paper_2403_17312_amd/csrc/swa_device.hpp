@@ -175,6 +175,27 @@ __device__ __forceinline__ void store16(void* p, const Vec16& v) { *reinterpret_
 
 // ---- wave / block reductions -------------------------------------------------
 
+// Cross-lane move on the VALU data-parallel-primitive path (no LDS traffic).
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v)
+{
+    return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over aligned groups of LANES consecutive lanes (8, 16 or 32); every lane of the
+// group gets the total.  quad_perm swaps (xor 1, xor 2), then mirrors within 8 and
+// within 16 lanes; only the 32-lane case needs one LDS-routed exchange.
+template <int LANES>
+__device__ __forceinline__ float group_sum(float v)
+{
+    v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
+    v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
+    v += dpp_move<0x141>(v);   // row_half_mirror
+    if (LANES >= 16) v += dpp_move<0x140>(v);   // row_mirror
+    if (LANES >= 32) v += __shfl_xor(v, 16, 64);
+    return v;
+}
+
 __device__ __forceinline__ float wave_sum(float v)
 {
 #pragma unroll
