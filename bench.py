@@ -1,9 +1,11 @@
 #!/usr/bin/env python3
 """Benchmark of the SWA decode hot path on one MI355X.
 
-A "step" is one pass of the whole hot path over one batch: swa_decode_step
-(append, scores, softmax, importance accumulation, selection, sparse output)
-followed by swa_compact_kv, for all b*h (sequence, head) pairs of one layer.
+A "step" is one pass of the whole hot path over one batch: append, scores,
+softmax, importance accumulation, selection, sparse output and in-place
+compaction, for all b*h (sequence, head) pairs of one layer.  By default that is
+ONE kernel (swa_decode_step with SWA_FUSE_COMPACTION); --step-mode split runs
+swa_decode_step followed by swa_compact_kv instead.
 
 The timed region walks complete decode trajectories of the workload (first
 step right after the prompt, then the steady state with compaction every
@@ -51,7 +53,9 @@ def simulate_lengths(B, wl, lens):
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
-    def __init__(self, B, W, wl, prompt, torch, len_bounds):
+    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused):
+        self.fused = fused
+        flags = B.SWA_FUSE_COMPACTION if fused else 0
         params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
         st.K.copy_(prompt["K"])
@@ -63,17 +67,31 @@ class Replica:
         self.seq_lens = torch.stack([base + (t + 1) for t in range(wl.steps)]).contiguous()  # [T, b]
         # per-step params: the host knows an upper bound on the cached length of every step
         self.params = [B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype,
-                                     len_bound=lb) for lb in len_bounds]
+                                     len_bound=lb, flags=flags) for lb in len_bounds]
+
+    def decode(self, B, t, q, kn, vn):
+        st = self.st
+        if self.fused:
+            # one kernel: the new lengths come back in kept_cnt, so the two arrays alternate
+            B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+                              self.seq_lens[t], None, st.kept_cnt, st.out, None, st.workspace)
+            st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
+        else:
+            B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
+                              self.seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+
+    def compact(self, B, t):
+        st = self.st
+        if not self.fused:
+            B.swa_compact_kv(self.params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
+                             st.cache_len, st.workspace)
 
     def step(self, B, t, q, kn, vn):
-        st = self.st
-        B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
-                          self.seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
-        B.swa_compact_kv(self.params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
-                         st.cache_len, st.workspace)
+        self.decode(B, t, q, kn, vn)
+        self.compact(B, t)
 
 
-def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True, log=None):
+def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True):
     dev = "cuda"
     T = wl.steps
     R = max(1, math.ceil(steps / T))
@@ -86,7 +104,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True,
     len_bounds = [max(m_t) for m_t in ms]
 
     def fresh(n):
-        reps = [Replica(B, W, wl, prompt, torch, len_bounds) for _ in range(n)]
+        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused) for _ in range(n)]
         if q_tail is not None:
             for r in reps:
                 r.st.prefill_scores(q_tail)
@@ -157,7 +175,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True,
             alg_bytes += wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
 
     res = {
-        "workload": wl.name, "steps": steps, "replicas": R, "mode": mode,
+        "workload": wl.name, "steps": steps, "replicas": R, "mode": mode, "fused": fused,
         "ms_per_step": total_ms / steps, "total_ms": total_ms, "host_wall_ms": wall_ms,
         "kv_tokens_per_s": kv_tokens / (total_ms * 1e-3),
         "generated_tokens_per_s": wl.b * steps / (total_ms * 1e-3),
@@ -182,17 +200,14 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, want_kernel_times=True,
         for i in range(steps):
             t, r = divmod(i, n)
             q, kn, vn = inputs[t]
-            st = reps[r].st
             ev[i][0].record()
-            B.swa_decode_step(reps[r].params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
-                              reps[r].seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+            reps[r].decode(B, t, q, kn, vn)
             ev[i][1].record()
-            B.swa_compact_kv(reps[r].params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
-                             st.cache_len, st.workspace)
+            reps[r].compact(B, t)
             ev[i][2].record()
         torch.cuda.synchronize()
         dec = [max(0.0, e[0].elapsed_time(e[1]) - empty_ms) for e in ev]
-        cmp_ = [max(0.0, e[1].elapsed_time(e[2]) - empty_ms) for e in ev]
+        cmp_ = [max(0.0, e[1].elapsed_time(e[2]) - empty_ms) if not fused else 0.0 for e in ev]
         res["decode_kernel_ms_avg"] = sum(dec) / steps
         res["compact_kernel_ms_avg"] = sum(cmp_) / steps
         res["event_pair_overhead_ms"] = empty_ms
@@ -265,6 +280,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default="c2_opt6p7b")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
+    ap.add_argument("--step-mode", choices=["fused", "split"], default="fused",
+                    help="fused: one kernel per step; split: swa_decode_step + swa_compact_kv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--others", default="c3_opt13b,c4_opt30b,c5_llama7b_sp80",
                     help="comma list of further workloads summarised in the same line ('' = none)")
@@ -285,7 +302,8 @@ def main():
     wl = W.CONFIGS[args.config]
     steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
     warmup = args.warmup if args.warmup is not None else wl.steps
-    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W)
+    fused = args.step_mode == "fused"
+    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused)
 
     dec_ms = res["decode_kernel_ms_avg"]
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
@@ -300,7 +318,8 @@ def main():
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
                    "replicas": res["replicas"], "launch": args.mode,
-                   "step": "swa_decode_step + swa_compact_kv"},
+                   "step": ("swa_decode_step with SWA_FUSE_COMPACTION (one kernel, kept_idx not requested)"
+                            if fused else "swa_decode_step + swa_compact_kv")},
         "roofline": {
             "bound": "hbm", "kernel": "swa_decode_kernel",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -321,7 +340,7 @@ def main():
     for name in [x for x in args.others.split(",") if x and x != args.config]:
         o = W.CONFIGS[name]
         k = o.steps * max(1, 256 // o.steps)
-        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W)
+        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused)
         a = r["alg_bytes_per_step"] / (r["decode_kernel_ms_avg"] * 1e-3) / 1e9
         others.append({"workload": name, "steps": k, "kv_tokens_per_s": r["kv_tokens_per_s"],
                        "ms_per_step": r["ms_per_step"], "decode_kernel_ms_avg": r["decode_kernel_ms_avg"],

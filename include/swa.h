@@ -68,7 +68,25 @@ typedef struct {
                             call: lets swa_decode_step size its LDS to the live cache instead of
                             cap.  A sequence that exceeds it is skipped and reported exactly like
                             a full cache (capacity status bit). */
+    int32_t flags;       /* 0 or SWA_FUSE_COMPACTION */
 } swa_params;
+
+/*
+ * swa_params.flags bit: swa_decode_step also compacts the cache (the work of
+ * swa_compact_kv) inside the same kernel.  In this mode
+ *   - cache_len is only READ; the new length of sequence s is written to kept_cnt[s]
+ *     (kept_cnt[s] = cache_len[s] for a skipped sequence).  The caller passes the two arrays
+ *     swapped on the next call.  (Publishing the length through the array that the same
+ *     launch reads would need a grid-wide ordering; a second array needs none.)
+ *   - on return the kept rows of k_cache, v_cache, score and pos sit in slots 0..kept_cnt-1,
+ *     order preserved; swa_compact_kv must not be called for this step;
+ *   - kept_idx may be NULL; when given it receives the ascending list of PRE-compaction
+ *     slots that were kept, as in the unfused call.
+ *   - LDS holds 16 bytes per live slot instead of 8: len_bound (or cap) above 9216 is
+ *     refused with SWA_ERR_CAPACITY.
+ */
+#define SWA_FUSE_COMPACTION 1
+#define SWA_MAX_FUSED_SLOTS 9216
 
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);
@@ -128,7 +146,7 @@ int swa_prefill_scores(const swa_params *params, const void *q_tail, int32_t R,
  * swa_compact_kv is legal (all m slots stay candidates).
  *   q, k_new, v_new [b,h,d] (in); k_cache, v_cache, score, pos (in/out);
  *   cache_len [b] (in/out); seq_len [b] (in) logical length n counting this token;
- *   kept_idx, kept_cnt, out [b,h,d] (out);
+ *   kept_idx, kept_cnt, out [b,h,d] (out); see SWA_FUSE_COMPACTION for the fused variant;
  *   probs_dbg [b,h,cap] float32 or NULL: receives p (0 beyond m) when given.
  * A sequence with cache_len[s] + 1 > cap is skipped (nothing written for it)
  * and the capacity status bit is set.

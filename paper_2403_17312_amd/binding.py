@@ -22,6 +22,8 @@ SWA_ERR_NULL, SWA_ERR_BAD_SHAPE, SWA_ERR_UNSUPPORTED_D, SWA_ERR_UNSUPPORTED_DTYP
 SWA_ERR_BAD_SPARSITY, SWA_ERR_CAPACITY, SWA_ERR_HIP, SWA_ERR_ALIGNMENT = -5, -6, -7, -8
 SWA_MAX_CAP = 16384
 SWA_MAX_PREFILL_ROWS = 128
+SWA_FUSE_COMPACTION = 1
+SWA_MAX_FUSED_SLOTS = 9216
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
@@ -32,7 +34,7 @@ class SwaParams(ctypes.Structure):
     _fields_ = [("b", ctypes.c_int32), ("h", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("cap", ctypes.c_int32), ("w", ctypes.c_int32), ("sparsity_bp", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
-                ("len_bound", ctypes.c_int32)]
+                ("len_bound", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class SwaError(RuntimeError):
@@ -80,9 +82,9 @@ def strerror(code: int) -> str:
 
 
 def make_params(b: int, h: int, d: int, cap: int, w: int, sparsity_bp: int, dtype,
-                scale: float = 0.0, len_bound: int = 0) -> SwaParams:
+                scale: float = 0.0, len_bound: int = 0, flags: int = 0) -> SwaParams:
     code = DTYPE_CODE[dtype] if isinstance(dtype, torch.dtype) else int(dtype)
-    return SwaParams(b, h, d, cap, w, sparsity_bp, code, scale, len_bound)
+    return SwaParams(b, h, d, cap, w, sparsity_bp, code, scale, len_bound, flags)
 
 
 def _ptr(t: Optional[torch.Tensor]):
@@ -176,6 +178,14 @@ class DecodeState:
         swa_decode_step(self.params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
                         self.cache_len, self.seq_len, self.kept_idx, self.kept_cnt, self.out,
                         self.probs, self.workspace, stream)
+
+    def decode_compact_step(self, q, k_new, v_new, stream=None, want_idx: bool = True) -> None:
+        """Fused call (params.flags must carry SWA_FUSE_COMPACTION): the new lengths come back in
+        kept_cnt, so the two length tensors are swapped afterwards."""
+        swa_decode_step(self.params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
+                        self.cache_len, self.seq_len, self.kept_idx if want_idx else None,
+                        self.kept_cnt, self.out, self.probs, self.workspace, stream)
+        self.cache_len, self.kept_cnt = self.kept_cnt, self.cache_len
 
     def compact(self, stream=None) -> None:
         swa_compact_kv(self.params, self.K, self.V, self.score, self.pos, self.kept_idx,

@@ -66,6 +66,7 @@ static int validate(const swa_params* p)
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
     if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
+    if (p->flags & ~SWA_FUSE_COMPACTION) return SWA_ERR_BAD_SHAPE;
     return SWA_OK;
 }
 
@@ -160,9 +161,15 @@ int swa_decode_step(const swa_params* params, const void* q, const void* k_new, 
 {
     int rc = swa::validate(params);
     if (rc != SWA_OK) return rc;
+    const bool fuse = (params->flags & SWA_FUSE_COMPACTION) != 0;
     if (!q || !k_new || !v_new || !k_cache || !v_cache || !score || !pos || !cache_len || !seq_len ||
-        !kept_idx || !kept_cnt || !out || !workspace)
+        (!kept_idx && !fuse) || !kept_cnt || !out || !workspace)
         return SWA_ERR_NULL;
+    if (fuse) {
+        const int bound = (params->len_bound > 0 && params->len_bound < params->cap) ? params->len_bound : params->cap;
+        if (bound > SWA_MAX_FUSED_SLOTS) return SWA_ERR_CAPACITY;
+        if (cache_len == kept_cnt) return SWA_ERR_BAD_SHAPE;
+    }
     if (!swa::aligned16(q) || !swa::aligned16(k_new) || !swa::aligned16(v_new) || !swa::aligned16(k_cache) ||
         !swa::aligned16(v_cache) || !swa::aligned16(out))
         return SWA_ERR_ALIGNMENT;

@@ -46,6 +46,7 @@ struct DecodeArgs {
     int32_t* arrive;
     int32_t h, cap, lds_slots, w, sparsity_bp;
     float scale;
+    int32_t fuse_compaction;
 };
 
 constexpr int kMaxFix = 8;           // evicted rows the subtractive schedule handles
@@ -94,6 +95,11 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     // only after key j' >= j of the same or a later tile has been read (see the ordered
     // compaction below), and the keys are dead once the list is complete.
     uint16_t* s_kept = reinterpret_cast<uint16_t*>(s_key);
+    // Fused compaction only: the new importance values and the old positions wait in LDS
+    // until the selection is known, then go straight to their compacted slots.
+    float* s_sc = reinterpret_cast<float*>(s_key + a.lds_slots);
+    int32_t* s_pos = reinterpret_cast<int32_t*>(s_sc + a.lds_slots);
+    const bool fc = a.fuse_compaction != 0;
     __shared__ float s_redA[16];
     __shared__ float s_redB[16];
     __shared__ unsigned long long s_red64[16];
@@ -126,6 +132,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         char* Kp = a.k_cache + pair * (int64_t)cap * ROWB;
         char* Vp = a.v_cache + pair * (int64_t)cap * ROWB;
         float* Sp = a.score + pair * (int64_t)cap;
+        int32_t* Pp = a.pos + pair * (int64_t)cap;
         const char* knew = a.k_new + pair * ROWB;
         const char* vnew = a.v_new + pair * ROWB;
 
@@ -141,18 +148,24 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             const int i = tid + k * NT;
             sold[k] = (i < len) ? Sp[i] : 0.f;
         }
+        int32_t pold[SPF];
+#pragma unroll
+        for (int k = 0; k < SPF; ++k) {
+            const int i = tid + k * NT;
+            pold[k] = (fc && i < len) ? Pp[i] : (n - 1);
+        }
 
-        // ---- append ---------------------------------------------------------------
-        if (tid < LPR) {
-            store16(Kp + (int64_t)len * ROWB + tid * 16, load16(knew + tid * 16));
-        } else if (tid < 2 * LPR) {
-            const int t2 = tid - LPR;
-            store16(Vp + (int64_t)len * ROWB + t2 * 16, load16(vnew + t2 * 16));
+        // ---- append (with fused compaction the new row goes straight to its final slot) ----
+        if (!fc) {
+            if (tid < LPR) {
+                store16(Kp + (int64_t)len * ROWB + tid * 16, load16(knew + tid * 16));
+            } else if (tid < 2 * LPR) {
+                const int t2 = tid - LPR;
+                store16(Vp + (int64_t)len * ROWB + t2 * 16, load16(vnew + t2 * 16));
+            }
+            if (tid == 0) Pp[len] = n - 1;
         }
-        if (tid == 0) {
-            a.pos[pair * (int64_t)cap + len] = n - 1;
-            s_ecnt = 0;
-        }
+        if (tid == 0) s_ecnt = 0;
 
         QFrag<T> qf;
         qf.load(load16(a.q + pair * ROWB + sub * 16));
@@ -295,7 +308,12 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 const float p = s_p[i] / sum;
                 s_p[i] = p;
                 const float sc = sold[k] + p;
-                Sp[i] = sc;
+                if (fc) {
+                    s_sc[i] = sc;
+                    s_pos[i] = pold[k];
+                } else {
+                    Sp[i] = sc;
+                }
                 const uint32_t key = order_key(sc);
                 s_key[i] = key;
                 if (i < ncand) {
@@ -309,7 +327,12 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             s_p[i] = p;
             const float old = (i == len) ? 0.f : Sp[i];
             const float sc = old + p;
-            Sp[i] = sc;
+            if (fc) {
+                s_sc[i] = sc;
+                s_pos[i] = (i == len) ? (n - 1) : Pp[i];
+            } else {
+                Sp[i] = sc;
+            }
             const uint32_t key = order_key(sc);
             s_key[i] = key;
             if (i < ncand) {
@@ -324,10 +347,12 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         }
 
         // ---- selection ---------------------------------------------------------------------
-        int32_t* kout = a.kept_idx + pair * (int64_t)cap;
+        int32_t* kout = a.kept_idx ? a.kept_idx + pair * (int64_t)cap : nullptr;
         bool have_list = false;           // s_kept holds the kept list
+        int jstar = m;                    // E <= 1: the evicted slot (m = none)
         if (E == 0) {
-            for (int i = tid; i < m; i += NT) kout[i] = i;
+            if (kout)
+                for (int i = tid; i < m; i += NT) kout[i] = i;
             __syncthreads();
         } else if (E == 1 && n_global > 0) {
             // evict the single candidate that loses: lowest score, ties -> highest slot
@@ -341,8 +366,9 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             best = s_red64[0];
 #pragma unroll
             for (int v = 1; v < NW; ++v) best = s_red64[v] < best ? s_red64[v] : best;
-            const int jstar = (int)(~(uint32_t)(best & 0xffffffffull));
-            for (int j = tid; j < keep; j += NT) kout[j] = j + (j >= jstar ? 1 : 0);
+            jstar = (int)(~(uint32_t)(best & 0xffffffffull));
+            if (kout)
+                for (int j = tid; j < keep; j += NT) kout[j] = j + (j >= jstar ? 1 : 0);
             if (tid == 0) {
                 s_evict[0] = jstar;
                 s_ecnt = 1;
@@ -432,7 +458,8 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 run_out += k_all;
                 __syncthreads();
             }
-            for (int j = tid; j < keep; j += NT) kout[j] = s_kept[j];
+            if (kout)
+                for (int j = tid; j < keep; j += NT) kout[j] = s_kept[j];
         }
 
         // ---- output ---------------------------------------------------------------------------
@@ -485,9 +512,9 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         } else {
             // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i
             if (!have_list) {
-                // the E <= 1 paths wrote the list straight to HBM; rebuild it in LDS
-                const int jstar = (E == 1 && n_global > 0) ? s_evict[0] : m;
+                // the E <= 1 paths did not build the list in LDS; do it now
                 for (int j = tid; j < keep; j += NT) s_kept[j] = (uint16_t)(j + (j >= jstar ? 1 : 0));
+                have_list = true;
             }
             __syncthreads();
 #pragma unroll
@@ -546,6 +573,72 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
             }
         }
+
+        // ---- fused compaction: kept rows of K, V, score, pos go to slots 0..keep-1 -----------
+        if (fc) {
+            __syncthreads();   // s_sc, s_pos and the kept list of every thread are in LDS
+            // final slot j holds the token of pre-compaction slot src(j); src(j) >= j
+            auto src_of = [&](int j) -> int { return have_list ? (int)s_kept[j] : j + (j >= jstar ? 1 : 0); };
+            for (int j = tid; j < keep; j += NT) {
+                const int src = src_of(j);
+                Sp[j] = s_sc[src];
+                if (src != j || src == len) Pp[j] = s_pos[src];
+            }
+            // rows only move down; the prefix with src(j) == j stays (the new row always
+            // counts as moved: it comes from k_new / v_new)
+            int j0;
+            if (have_list) {
+                int lo = 0, hi = keep;
+                while (lo < hi) {
+                    const int mid = (lo + hi) >> 1;
+                    const int sm = (int)s_kept[mid];
+                    if (sm == mid && sm != len) lo = mid + 1; else hi = mid;
+                }
+                j0 = lo;
+            } else {
+                j0 = jstar < len ? jstar : len;
+            }
+            constexpr int UC = 2;
+            constexpr int CH = NG * UC;
+            for (int c0 = j0; c0 < keep; c0 += CH) {
+                Vec16 kk[UC], vv2[UC];
+                int dst[UC];
+#pragma unroll
+                for (int u = 0; u < UC; ++u) {
+                    const int j = c0 + u * NG + grp;
+                    dst[u] = -1;
+                    if (j < keep) {
+                        int src = src_of(j);
+                        src = src < 0 ? 0 : (src > len ? len : src);
+                        const char* ks = (src == len) ? knew : Kp + (int64_t)src * ROWB;
+                        const char* vs = (src == len) ? vnew : Vp + (int64_t)src * ROWB;
+                        kk[u] = load16(ks + sub * 16);
+                        vv2[u] = load16(vs + sub * 16);
+                        dst[u] = j;
+                    }
+                }
+                // every source of the chunk is in registers before any destination is written
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                __syncthreads();
+#pragma unroll
+                for (int u = 0; u < UC; ++u) {
+                    if (dst[u] >= 0) {
+                        store16(Kp + (int64_t)dst[u] * ROWB + sub * 16, kk[u]);
+                        store16(Vp + (int64_t)dst[u] * ROWB + sub * 16, vv2[u]);
+                    }
+                }
+            }
+        }
+    }
+
+    if (fc) {
+        // The new length is published through kept_cnt (every head writes the same value);
+        // cache_len is only read, so no workgroup can observe a half-updated step.
+        if (tid == 0) {
+            if (overflow) atomicOr(a.status, kStatusCapacityBit);
+            a.kept_cnt[s] = overflow ? len : keep;
+        }
+        return;
     }
 
     // ---- per-sequence arrival: the last head to finish publishes the new length --------
@@ -614,9 +707,10 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.w = p.w;
     a.sparsity_bp = p.sparsity_bp;
     a.scale = scale;
+    a.fuse_compaction = (p.flags & SWA_FUSE_COMPACTION) ? 1 : 0;
 
     const int64_t pairs = (int64_t)p.b * p.h;
-    const size_t lds_bytes = (size_t)a.lds_slots * 8;
+    const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? 16 : 8);
     const int nt = decode_block_threads(pairs);
 
     if (p.dtype == SWA_F32) {

@@ -52,8 +52,10 @@ class Workload:
 
     @property
     def cap(self) -> int:
-        """Slots per (sequence, head): room for the prompt plus every decode token."""
-        return self.prompt_hi + self.steps + 1
+        """Slots per (sequence, head): room for the prompt plus every decode token, rounded up to
+        a multiple of 64 so that every pair's rows of the fp32/int32 side arrays start on a
+        256-byte boundary."""
+        return (self.prompt_hi + self.steps + 1 + 63) // 64 * 64
 
     @property
     def scale(self) -> float:

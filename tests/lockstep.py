@@ -80,7 +80,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
                  prompt: Optional[dict] = None, verbose: bool = False,
-                 use_len_bound: bool = False) -> Report:
+                 use_len_bound: bool = False, fused: bool = False) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
@@ -88,6 +88,10 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
     prompt = W.make_prompt(wl, device, slack=slack) if prompt is None else prompt
     st = new_state(wl, prompt)
     rep = Report(pairs=len(seqs) * len(heads))
+    if fused:
+        # swa_decode_step with SWA_FUSE_COMPACTION: one kernel does the step and the compaction
+        assert compact_every == 1
+        st.params.flags = B.SWA_FUSE_COMPACTION
     seqs_t = torch.tensor(seqs, device=device)
     heads_t = torch.tensor(heads, device=device)
 
@@ -119,7 +123,11 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         if use_len_bound:
             # exact bound: the longest cache of this step, from the host's replay of the budget
             st.params.len_bound = max(host_len) + 1
-        st.decode_step(q, kn, vn)
+        if fused:
+            score_prev32 = _sub(st.score, seqs_t, heads_t).cpu().numpy().astype(np.float32)
+            st.decode_compact_step(q, kn, vn)        # swaps cache_len / kept_cnt afterwards
+        else:
+            st.decode_step(q, kn, vn)
         for s_i in range(wl.b):
             m_i = host_len[s_i] + 1
             host_len[s_i] = (B.swa_budget(prompt["lengths"][s_i] + t + 1, m_i, wl.w, wl.sparsity_bp)[0]
@@ -131,10 +139,27 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
         kept_o, cnt_o, out_o, p_o = O.decode_step(q_o, kn_o, vn_o, K_o, V_o, score_o, pos_o, len_o,
                                                   n_o, wl.w, wl.sparsity_bp, wl.scale)
-        score_g = _np64(_sub(st.score, seqs_t, heads_t))
         kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
-        cnt_g = st.kept_cnt[seqs_t].cpu().numpy()
-        assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o), f"step {t}: cache_len"
+        if fused:
+            # the cache is already compacted: the new lengths are in cache_len (swapped in),
+            # and the GPU's pre-compaction importance vector is rebuilt exactly as the kernel
+            # formed it, fp32(old + p), from the adopted fp32 state and the fp32 weights
+            cnt_g = st.cache_len[seqs_t].cpu().numpy()
+            p32 = _sub(st.probs, seqs_t, heads_t).cpu().numpy().astype(np.float32)
+            full32 = score_prev32.copy()
+            for i, m in enumerate(len_o):
+                full32[i, :, m - 1] = 0.0                      # the new token starts at zero
+                full32[i, :, :m] = (full32[i, :, :m] + p32[i, :, :m]).astype(np.float32)
+            score_g = full32.astype(np.float64)
+            comp32 = _sub(st.score, seqs_t, heads_t).cpu().numpy()
+            for i, c in enumerate(cnt_g):
+                for hd in range(len(heads)):
+                    assert np.array_equal(comp32[i, hd, :c], full32[i, hd, kept_g[i, hd, :c]]), \
+                        f"step {t}: compacted importance is not fp32(old + p) of the kept slots"
+        else:
+            score_g = _np64(_sub(st.score, seqs_t, heads_t))
+            cnt_g = st.kept_cnt[seqs_t].cpu().numpy()
+            assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o), f"step {t}: cache_len"
         assert np.array_equal(cnt_g, cnt_o), f"step {t}: kept_cnt {cnt_g} vs {cnt_o}"
 
         if do_check:
@@ -183,7 +208,8 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             for i, c in enumerate(cnt_g):
                 for hd in range(len(heads)):
                     rep.moved_rows += int(np.sum(kept_g[i, hd, :c] != np.arange(c)))
-            st.compact()
+            if not fused:
+                st.compact()
             O.compact(K_o, V_o, score_o, pos_o, kept_g, cnt_g, len_o)
             assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o)
             if do_check:

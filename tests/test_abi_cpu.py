@@ -39,9 +39,11 @@ def test_params_struct_matches_header(B):
     body = re.sub(r"/\*.*?\*/", "", body, flags=re.S)
     fields = re.findall(r"(int32_t|float)\s+(\w+);", body)
     assert [f[1] for f in fields] == [f[0] for f in B.SwaParams._fields_]
-    assert ctypes.sizeof(B.SwaParams) == 36
+    assert ctypes.sizeof(B.SwaParams) == 40
     assert int(re.search(r"#define SWA_MAX_CAP (\d+)", text).group(1)) == B.SWA_MAX_CAP
     assert int(re.search(r"#define SWA_MAX_PREFILL_ROWS (\d+)", text).group(1)) == B.SWA_MAX_PREFILL_ROWS
+    assert int(re.search(r"#define SWA_MAX_FUSED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_FUSED_SLOTS
+    assert int(re.search(r"#define SWA_FUSE_COMPACTION (\d+)", text).group(1)) == B.SWA_FUSE_COMPACTION
 
 
 def test_strerror_covers_all_codes(B):
@@ -77,12 +79,13 @@ def test_workspace_bytes(B):
     (dict(cap=0), "SWA_ERR_BAD_SHAPE"),
     (dict(cap=16385), "SWA_ERR_CAPACITY"),
     (dict(len_bound=-1), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=2), "SWA_ERR_BAD_SHAPE"),
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
     (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),
 ])
 def test_bad_params_are_rejected_before_any_device_work(B, kw, code):
-    base = dict(b=2, h=2, d=64, cap=32, w=2, sparsity_bp=5000, dtype=B.SWA_F32, scale=0.0, len_bound=0)
+    base = dict(b=2, h=2, d=64, cap=32, w=2, sparsity_bp=5000, dtype=B.SWA_F32, scale=0.0, len_bound=0, flags=0)
     base.update(kw)
     p = B.SwaParams(*[base[f[0]] for f in B.SwaParams._fields_])
     L = B.lib()
@@ -107,6 +110,18 @@ def test_null_and_misaligned_pointers_are_rejected(B):
     a[3] = ctypes.c_void_p(0x1008)
     assert L.swa_decode_step(ctypes.byref(p), *a) == B.SWA_ERR_ALIGNMENT
     assert L.swa_decode_step(None, *args) == B.SWA_ERR_NULL
+    # fused compaction: kept_idx may be NULL, the two length arrays must differ, LDS bound applies
+    pf = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F32, flags=B.SWA_FUSE_COMPACTION)
+    a = list(args)
+    a[7] = ctypes.c_void_p(0x2000)
+    a[9] = None
+    a[0] = None                                               # still rejects a missing q
+    assert L.swa_decode_step(ctypes.byref(pf), *a) == B.SWA_ERR_NULL
+    a = list(args)                                            # cache_len == kept_cnt
+    assert L.swa_decode_step(ctypes.byref(pf), *a) == B.SWA_ERR_BAD_SHAPE
+    pbig = B.make_params(2, 2, 64, 12000, 2, 5000, B.SWA_F32, flags=B.SWA_FUSE_COMPACTION)
+    a[7] = ctypes.c_void_p(0x2000)
+    assert L.swa_decode_step(ctypes.byref(pbig), *a) == B.SWA_ERR_CAPACITY
     assert L.swa_compact_kv(ctypes.byref(p), None, *([ok] * 8)) == B.SWA_ERR_NULL
     assert L.swa_prefill_scores(ctypes.byref(p), ok, 0, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
     assert L.swa_prefill_scores(ctypes.byref(p), ok, 129, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE

@@ -63,12 +63,36 @@ def test_c2_opt6p7b_every_pair_every_step(env):
     assert rep.steps == 32
 
 
+def test_fused_compaction_matches_the_two_call_path(env):
+    # swa_decode_step with SWA_FUSE_COMPACTION against the oracle's step + stable gather
+    O, B, W, LS = env
+    _say("c1 / c2 lockstep, fused compaction")
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"], fused=True)
+    assert rep.steps == 16 and rep.evictions > 0
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"].replace(prefill_R=8, w=0), fused=True)
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], fused=True, use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+    for dtype, d in [("f32", 128), ("bf16", 64), ("f16", 64)]:
+        wl = W.Workload(f"t_fc_{dtype}_{d}", 17, b=3, h=5, d=d, dtype=dtype, prompt_lo=2, prompt_hi=333,
+                        steps=12, w=7, sparsity_bp=7000, hh_frac=0.02, prefill_R=5)
+        LS.run_lockstep(wl, fused=True)
+    # sparsity 0 (nothing ever evicted), and a budget that evicts several tokens per step
+    LS.run_lockstep(W.Workload("t_fc_dense", 18, b=2, h=3, d=128, dtype="f16", prompt_lo=1, prompt_hi=90,
+                               steps=9, w=4, sparsity_bp=0, hh_frac=0.02), fused=True)
+    LS.run_lockstep(W.Workload("t_fc_w0", 19, b=2, h=3, d=128, dtype="f16", prompt_lo=50, prompt_hi=90,
+                               steps=9, w=0, sparsity_bp=9000, hh_frac=0.02), fused=True)
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
     _say("c3 lockstep (full size on the GPU, sampled pairs checked)")
     rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero",
                           use_len_bound=True)
+    _say(f"  {rep}")
+    rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero",
+                          use_len_bound=True, fused=True)
     _say(f"  {rep}")
     assert rep.steps == 64
 
@@ -78,6 +102,9 @@ def test_c4_opt30b_full_size_sampled_pairs_with_mfma_prefill(env):
     wl = W.CONFIGS["c4_opt30b"]
     _say("c4 lockstep (full size, bf16, MFMA prefill seed)")
     rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero", use_len_bound=True)
+    _say(f"  {rep}")
+    rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero", use_len_bound=True,
+                          fused=True)
     _say(f"  {rep}")
     assert rep.steps == 128
 
@@ -91,7 +118,7 @@ def test_c5_llama7b_full_size_sampled_pairs(env, name):
     _say(f"{name} lockstep (full size, mixed lengths {min(lens)}..{max(lens)}, seqs {seqs})")
     check = set(range(0, 256, 3)) | {1, 2, 254, 255}
     rep = LS.run_lockstep(wl, seqs=seqs, heads=[0, 15, 31], slack="zero", check_steps=check,
-                          use_len_bound=True)
+                          use_len_bound=True, fused=(name != "c5_llama7b_sp50"))
     _say(f"  {rep}")
     assert rep.steps == 256
     torch.cuda.empty_cache()
