@@ -28,7 +28,21 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes)
     return SWA_OK;
 }
 
-int decode_block_threads(int64_t pairs)
+int decode_stash_rows(const swa_params& p)
+{
+    // window + a margin for evictions a little behind it; bounded so LDS keeps several
+    // workgroups per CU; never more than the cache can hold
+    int rows = ((p.w + 16 + 15) / 16) * 16;
+    if (rows > 96) rows = 96;
+    const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
+    if (rows > bound) rows = ((bound + 15) / 16) * 16;
+    // long caches (first step after a prompt) take the gather schedule, which has no use for it
+    const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
+    if ((size_t)((bound + 63) & ~63) * 16 + (size_t)rows * rowb * 2 > 96 * 1024) rows = 0;
+    return rows;
+}
+
+int decode_block_threads(int64_t pairs, int len_bound)
 {
     // Tuning override (64, 128, 256 or 512), read once.
     static const int forced = [] {
@@ -37,8 +51,10 @@ int decode_block_threads(int64_t pairs)
         return (v == 64 || v == 128 || v == 256 || v == 512) ? v : 0;
     }();
     if (forced) return forced;
-    // Measured on MI355X: 256 threads once there are several pairs per CU, 128 below that.
-    return pairs >= 1024 ? 256 : 128;
+    // Measured on MI355X (all five workloads): long caches want 512 threads per pair, the
+    // short caches of the steady state 256; the pair count matters little.
+    (void)pairs;
+    return len_bound > 400 ? 512 : 256;
 }
 
 __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)

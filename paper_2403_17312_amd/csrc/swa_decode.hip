@@ -47,6 +47,7 @@ struct DecodeArgs {
     int32_t h, cap, lds_slots, w, sparsity_bp;
     float scale;
     int32_t fuse_compaction;
+    int32_t stash_rows;   // fused compaction: newest rows kept in LDS during the streaming pass
 };
 
 constexpr int kMaxFix = 8;           // evicted rows the subtractive schedule handles
@@ -99,6 +100,11 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     // until the selection is known, then go straight to their compacted slots.
     float* s_sc = reinterpret_cast<float*>(s_key + a.lds_slots);
     int32_t* s_pos = reinterpret_cast<int32_t*>(s_sc + a.lds_slots);
+    // ... and the newest stash_rows key/value rows are parked in LDS while they stream by: the
+    // token evicted in the steady state sits just behind the window, so the rows that have to
+    // move down (and the evicted row itself) are then served from LDS instead of being re-read.
+    char* s_stK = reinterpret_cast<char*>(s_pos + a.lds_slots);
+    char* s_stV = s_stK + (size_t)a.stash_rows * ROWB;
     const bool fc = a.fuse_compaction != 0;
     __shared__ float s_redA[16];
     __shared__ float s_redB[16];
@@ -140,6 +146,8 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         const int ncand = m - n_local;
         const int E = m - keep;                       // evictions of this step
         const bool fused = (E <= kMaxFix) && (8 * E <= m);
+        // first stashed slot (m = nothing stashed: only the streaming schedule fills the stash)
+        const int stash_lo = (fc && fused) ? (m > a.stash_rows ? m - a.stash_rows : 0) : m;
 
         // ---- importance prefetch: the old values are needed only after the softmax ----
         float sold[SPF];
@@ -205,6 +213,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 #pragma unroll
                 for (int u = 0; u < UF; ++u) {
                     const int row = base + u * NG + grp;
+                    if (row >= stash_lo && row < m) {
+                        store16(s_stK + (row - stash_lo) * ROWB + sub * 16, kv[u]);
+                        store16(s_stV + (row - stash_lo) * ROWB + sub * 16, vv[u]);
+                    }
                     if (sub == 0 && row < m) s_p[row] = z[u];
                     z[u] = (row < m) ? z[u] : -INFINITY;
                     mc = fmaxf(mc, z[u]);
@@ -356,11 +368,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             __syncthreads();
         } else if (E == 1 && n_global > 0) {
             // evict the single candidate that loses: lowest score, ties -> highest slot
-#pragma unroll
-            for (int o = 32; o > 0; o >>= 1) {
-                const unsigned long long t = __shfl_xor(best, o, kWave);
-                best = t < best ? t : best;
-            }
+            best = wave_min64(best);
             if (lane == 0) s_red64[wave] = best;
             __syncthreads();
             best = s_red64[0];
@@ -482,7 +490,8 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 int idx = s_evict[k];
                 idx = idx < 0 ? 0 : (idx > len ? len : idx);
                 const float pw = s_p[idx];
-                const char* vs = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
+                const char* vs = (idx >= stash_lo) ? s_stV + (idx - stash_lo) * ROWB
+                                                   : ((idx == len) ? vnew : Vp + (int64_t)idx * ROWB);
                 float f[EPV];
                 unpack<T>(load16(vs + sub * 16), f);
 #pragma unroll
@@ -598,7 +607,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             } else {
                 j0 = jstar < len ? jstar : len;
             }
-            constexpr int UC = 2;
+            constexpr int UC = 4;
             constexpr int CH = NG * UC;
             for (int c0 = j0; c0 < keep; c0 += CH) {
                 Vec16 kk[UC], vv2[UC];
@@ -610,15 +619,17 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     if (j < keep) {
                         int src = src_of(j);
                         src = src < 0 ? 0 : (src > len ? len : src);
-                        const char* ks = (src == len) ? knew : Kp + (int64_t)src * ROWB;
-                        const char* vs = (src == len) ? vnew : Vp + (int64_t)src * ROWB;
+                        const char* ks = (src >= stash_lo) ? s_stK + (src - stash_lo) * ROWB
+                                                           : ((src == len) ? knew : Kp + (int64_t)src * ROWB);
+                        const char* vs = (src >= stash_lo) ? s_stV + (src - stash_lo) * ROWB
+                                                           : ((src == len) ? vnew : Vp + (int64_t)src * ROWB);
                         kk[u] = load16(ks + sub * 16);
                         vv2[u] = load16(vs + sub * 16);
                         dst[u] = j;
                     }
                 }
                 // every source of the chunk is in registers before any destination is written
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
                 __syncthreads();
 #pragma unroll
                 for (int u = 0; u < UC; ++u) {
@@ -708,10 +719,12 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.sparsity_bp = p.sparsity_bp;
     a.scale = scale;
     a.fuse_compaction = (p.flags & SWA_FUSE_COMPACTION) ? 1 : 0;
+    a.stash_rows = a.fuse_compaction ? decode_stash_rows(p) : 0;
 
     const int64_t pairs = (int64_t)p.b * p.h;
-    const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? 16 : 8);
-    const int nt = decode_block_threads(pairs);
+    const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
+    const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? 16 : 8) + (size_t)a.stash_rows * rowb * 2;
+    const int nt = decode_block_threads(pairs, bound);
 
     if (p.dtype == SWA_F32) {
         return p.d == 64 ? launch_decode_t<F32, 64>(a, pairs, lds_bytes, nt, stream)

@@ -196,17 +196,51 @@ __device__ __forceinline__ float group_sum(float v)
     return v;
 }
 
+// Whole-wave reductions: four DPP steps inside each row of 16 lanes, then two LDS-routed
+// exchanges across the four rows.  Every lane gets the result.
 __device__ __forceinline__ float wave_sum(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    v = group_sum<16>(v);
+    v += __shfl_xor(v, 16, kWave);
+    v += __shfl_xor(v, 32, kWave);
     return v;
 }
 __device__ __forceinline__ float wave_max(float v)
 {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    v = fmaxf(v, dpp_move<0xB1>(v));
+    v = fmaxf(v, dpp_move<0x4E>(v));
+    v = fmaxf(v, dpp_move<0x141>(v));
+    v = fmaxf(v, dpp_move<0x140>(v));
+    v = fmaxf(v, __shfl_xor(v, 16, kWave));
+    v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
+}
+// Minimum of a 64-bit key held as (hi, lo), lexicographic.
+template <int CTRL>
+__device__ __forceinline__ void min64_dpp(uint32_t& hi, uint32_t& lo)
+{
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, 0xf, 0xf, true);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, CTRL, 0xf, 0xf, true);
+    const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
+    hi = take ? h2 : hi;
+    lo = take ? l2 : lo;
+}
+__device__ __forceinline__ unsigned long long wave_min64(unsigned long long v)
+{
+    uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    min64_dpp<0xB1>(hi, lo);
+    min64_dpp<0x4E>(hi, lo);
+    min64_dpp<0x141>(hi, lo);
+    min64_dpp<0x140>(hi, lo);
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+        const uint32_t h2 = (uint32_t)__shfl_xor((int)hi, o, kWave);
+        const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, o, kWave);
+        const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
+        hi = take ? h2 : hi;
+        lo = take ? l2 : lo;
+    }
+    return ((unsigned long long)hi << 32) | lo;
 }
 
 // All threads get the result.  `red` is an LDS array of at least blockDim.x/64 floats.

@@ -12,8 +12,12 @@ namespace swa {
 // Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.
 int ensure_dynamic_lds(const void* kernel, size_t bytes);
 
-// Threads per workgroup of the decode kernel for this many (sequence, head) pairs.
-int decode_block_threads(int64_t pairs);
+// Threads per workgroup of the decode kernel for this many (sequence, head) pairs and
+// this bound on the cached length.
+int decode_block_threads(int64_t pairs, int len_bound);
+
+// Rows of K and V the fused-compaction decode parks in LDS (0 = none).
+int decode_stash_rows(const swa_params& p);
 
 int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stream);
 
