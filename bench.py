@@ -295,7 +295,7 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
-    ap.add_argument("--others", default="c3_opt13b,c4_opt30b,c5_llama7b_sp80",
+    ap.add_argument("--others", default="c3_opt13b,c4_opt30b,c5_llama7b_sp50,c5_llama7b_sp80,c5_llama7b_sp90",
                     help="comma list of further workloads summarised in the same line ('' = none)")
     args = ap.parse_args()
     if args.gpus != 1:

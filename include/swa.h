@@ -68,7 +68,7 @@ typedef struct {
                             call: lets swa_decode_step size its LDS to the live cache instead of
                             cap.  A sequence that exceeds it is skipped and reported exactly like
                             a full cache (capacity status bit). */
-    int32_t flags;       /* 0 or SWA_FUSE_COMPACTION */
+    int32_t flags;       /* 0, SWA_FUSE_COMPACTION, or SWA_FUSE_COMPACTION | SWA_UNORDERED */
 } swa_params;
 
 /*
@@ -87,6 +87,22 @@ typedef struct {
  */
 #define SWA_FUSE_COMPACTION 1
 #define SWA_MAX_FUSED_SLOTS 9216
+
+/*
+ * swa_params.flags bit, only together with SWA_FUSE_COMPACTION: the compacted cache need not be
+ * in token order.  The method's result does not depend on the order of the cached rows once the
+ * window and the tie rule are stated on token positions, so in this mode
+ *   - the local window is the set of slots with pos >= seq_len - w (the most recent w tokens),
+ *     and ties of the top-k go to the EARLIEST token (lowest pos); for a cache in token order
+ *     both coincide with the slot-based rules of the ordered mode;
+ *   - compaction fills the holes below kept_cnt with the kept rows above it (in the steady
+ *     state the new token simply takes the evicted token's slot: no row moves at all);
+ *   - kept_idx[j], when given, is the PRE-compaction slot of the token that ends in slot j.
+ * pos must hold each slot's token position (it does after any sequence of calls that started
+ * from a cache filled in token order with pos = 0..len-1).  Up to 7168 live slots.
+ */
+#define SWA_UNORDERED 2
+#define SWA_MAX_UNORDERED_SLOTS 7168
 
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);

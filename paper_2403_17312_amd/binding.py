@@ -24,6 +24,8 @@ SWA_MAX_CAP = 16384
 SWA_MAX_PREFILL_ROWS = 128
 SWA_FUSE_COMPACTION = 1
 SWA_MAX_FUSED_SLOTS = 9216
+SWA_UNORDERED = 2
+SWA_MAX_UNORDERED_SLOTS = 7168
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",

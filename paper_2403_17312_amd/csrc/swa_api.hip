@@ -32,8 +32,13 @@ int decode_stash_rows(const swa_params& p)
 {
     // window + a margin for evictions a little behind it; bounded so LDS keeps several
     // workgroups per CU; never more than the cache can hold
+    static const int forced = [] {
+        const char* e = getenv("SWA_STASH_ROWS");   // tuning override, multiple of 16 in 0..96
+        return e ? atoi(e) : -1;
+    }();
     int rows = ((p.w + 16 + 15) / 16) * 16;
     if (rows > 96) rows = 96;
+    if (forced >= 0 && forced <= 96) rows = (forced / 16) * 16;
     const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
     if (rows > bound) rows = ((bound + 15) / 16) * 16;
     // long caches (first step after a prompt) take the gather schedule, which has no use for it
@@ -82,7 +87,8 @@ static int validate(const swa_params* p)
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
     if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
-    if (p->flags & ~SWA_FUSE_COMPACTION) return SWA_ERR_BAD_SHAPE;
+    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
+    if ((p->flags & SWA_UNORDERED) && !(p->flags & SWA_FUSE_COMPACTION)) return SWA_ERR_BAD_SHAPE;
     return SWA_OK;
 }
 
@@ -183,7 +189,7 @@ int swa_decode_step(const swa_params* params, const void* q, const void* k_new, 
         return SWA_ERR_NULL;
     if (fuse) {
         const int bound = (params->len_bound > 0 && params->len_bound < params->cap) ? params->len_bound : params->cap;
-        if (bound > SWA_MAX_FUSED_SLOTS) return SWA_ERR_CAPACITY;
+        if (bound > ((params->flags & SWA_UNORDERED) ? SWA_MAX_UNORDERED_SLOTS : SWA_MAX_FUSED_SLOTS)) return SWA_ERR_CAPACITY;
         if (cache_len == kept_cnt) return SWA_ERR_BAD_SHAPE;
     }
     if (!swa::aligned16(q) || !swa::aligned16(k_new) || !swa::aligned16(v_new) || !swa::aligned16(k_cache) ||

@@ -25,6 +25,9 @@
 // largest key, and an ordered ballot/popcount compaction writes the ascending
 // kept list with ties resolved towards the lowest slot.
 #include "swa_kernels.hpp"
+#ifndef SWA_UF
+#define SWA_UF 2
+#endif
 
 namespace swa {
 
@@ -47,6 +50,7 @@ struct DecodeArgs {
     int32_t h, cap, lds_slots, w, sparsity_bp;
     float scale;
     int32_t fuse_compaction;
+    int32_t unordered;    // fused compaction fills holes instead of shifting rows (order by pos only)
     int32_t stash_rows;   // fused compaction: newest rows kept in LDS during the streaming pass
 };
 
@@ -85,7 +89,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     constexpr int NG = NT / LPR;            // row groups per workgroup
     constexpr int ROWB = D * Elem<T>::kBytes;
     constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
-    constexpr int UF = 2;                   // key+value row pairs per group and pipeline stage (fused pass)
+    constexpr int UF = SWA_UF;              // key+value row pairs per group and pipeline stage (fused pass)
     constexpr int UV = 4;                   // value rows in flight per group (gathered pass)
     constexpr int SPF = 4;                  // importance values prefetched per thread
 
@@ -103,15 +107,21 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     // ... and the newest stash_rows key/value rows are parked in LDS while they stream by: the
     // token evicted in the steady state sits just behind the window, so the rows that have to
     // move down (and the evicted row itself) are then served from LDS instead of being re-read.
-    char* s_stK = reinterpret_cast<char*>(s_pos + a.lds_slots);
-    char* s_stV = s_stK + (size_t)a.stash_rows * ROWB;
     const bool fc = a.fuse_compaction != 0;
+    const bool bag = a.unordered != 0;
+    // Unordered compaction only: source slot of every final slot, the holes below `keep` and the
+    // kept rows above it that fill them (at most half of the slots each).
+    uint16_t* s_src = reinterpret_cast<uint16_t*>(s_pos + a.lds_slots);
+    uint16_t* s_holes = s_src + a.lds_slots;
+    uint16_t* s_movers = s_holes + a.lds_slots / 2;
+    char* s_stK = reinterpret_cast<char*>(s_pos + a.lds_slots) + (bag ? (size_t)a.lds_slots * 4 : 0);
+    char* s_stV = s_stK + (size_t)a.stash_rows * ROWB;
     __shared__ float s_redA[16];
     __shared__ float s_redB[16];
     __shared__ unsigned long long s_red64[16];
     __shared__ int32_t s_hist[256];
     __shared__ int32_t s_wcnt[2][16];
-    __shared__ int32_t s_sel[2];
+    __shared__ int32_t s_sel[3];
     __shared__ float s_acc[NW * D];
     __shared__ float s_wS[16];
     __shared__ float s_fix[kMaxFix * D];
@@ -144,6 +154,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 
         budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global);
         const int ncand = m - n_local;
+        const int wlo = n - a.w;                      // unordered layout: the window is pos >= wlo
         const int E = m - keep;                       // evictions of this step
         const bool fused = (E <= kMaxFix) && (8 * E <= m);
         // first stashed slot (m = nothing stashed: only the streaming schedule fills the stash)
@@ -312,7 +323,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         for (int v = 0; v < NW; ++v) sum += s_redB[v];
 
         // ---- importance accumulation; arg-min bookkeeping for the E == 1 case ------------
-        unsigned long long best = ~0ull;   // (key << 32 | ~slot): min = lowest score, highest slot
+        // (key << 32 | ~t): min = lowest score, then highest t; t is the slot, or the token
+        // position when slots are unordered.  The slot rides along as payload.
+        unsigned long long best = ~0ull;
+        int bslot = m;
 #pragma unroll
         for (int k = 0; k < SPF; ++k) {
             const int i = tid + k * NT;
@@ -328,9 +342,13 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 }
                 const uint32_t key = order_key(sc);
                 s_key[i] = key;
-                if (i < ncand) {
-                    const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)i);
-                    best = c < best ? c : best;
+                if (bag ? (pold[k] < wlo) : (i < ncand)) {
+                    const uint32_t t = bag ? (uint32_t)pold[k] : (uint32_t)i;
+                    const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~t);
+                    if (c < best) {
+                        best = c;
+                        bslot = i;
+                    }
                 }
             }
         }
@@ -339,17 +357,22 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             s_p[i] = p;
             const float old = (i == len) ? 0.f : Sp[i];
             const float sc = old + p;
+            const int posi = (fc && i < len) ? Pp[i] : (n - 1);
             if (fc) {
                 s_sc[i] = sc;
-                s_pos[i] = (i == len) ? (n - 1) : Pp[i];
+                s_pos[i] = posi;
             } else {
                 Sp[i] = sc;
             }
             const uint32_t key = order_key(sc);
             s_key[i] = key;
-            if (i < ncand) {
-                const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)i);
-                best = c < best ? c : best;
+            if (bag ? (posi < wlo) : (i < ncand)) {
+                const uint32_t t = bag ? (uint32_t)posi : (uint32_t)i;
+                const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~t);
+                if (c < best) {
+                    best = c;
+                    bslot = i;
+                }
             }
         }
         if (a.probs_dbg) {
@@ -362,21 +385,34 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         int32_t* kout = a.kept_idx ? a.kept_idx + pair * (int64_t)cap : nullptr;
         bool have_list = false;           // s_kept holds the kept list
         int jstar = m;                    // E <= 1: the evicted slot (m = none)
+        int n_moves = 0;                  // unordered layout: rows that change slot
         if (E == 0) {
             if (kout)
                 for (int i = tid; i < m; i += NT) kout[i] = i;
             __syncthreads();
         } else if (E == 1 && n_global > 0) {
-            // evict the single candidate that loses: lowest score, ties -> highest slot
-            best = wave_min64(best);
-            if (lane == 0) s_red64[wave] = best;
+            // evict the single candidate that loses: lowest score, ties -> the latest token
+            wave_min64p(best, bslot);
+            if (lane == 0) {
+                s_red64[wave] = best;
+                s_wcnt[0][wave] = bslot;
+            }
             __syncthreads();
             best = s_red64[0];
+            jstar = s_wcnt[0][0];
 #pragma unroll
-            for (int v = 1; v < NW; ++v) best = s_red64[v] < best ? s_red64[v] : best;
-            jstar = (int)(~(uint32_t)(best & 0xffffffffull));
-            if (kout)
-                for (int j = tid; j < keep; j += NT) kout[j] = j + (j >= jstar ? 1 : 0);
+            for (int v = 1; v < NW; ++v) {
+                if (s_red64[v] < best) {
+                    best = s_red64[v];
+                    jstar = s_wcnt[0][v];
+                }
+            }
+            jstar = jstar < 0 ? 0 : (jstar > len ? len : jstar);
+            if (kout) {
+                // ordered: the rows behind the hole shift down; unordered: the new row fills it
+                for (int j = tid; j < keep; j += NT)
+                    kout[j] = bag ? (j == jstar ? len : j) : j + (j >= jstar ? 1 : 0);
+            }
             if (tid == 0) {
                 s_evict[0] = jstar;
                 s_ecnt = 1;
@@ -392,9 +428,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 for (int shift = 24; shift >= 0; shift -= 8) {
                     for (int i = tid; i < 256; i += NT) s_hist[i] = 0;
                     __syncthreads();
-                    for (int i = tid; i < ncand; i += NT) {
+                    for (int i = tid; i < m; i += NT) {
                         const uint32_t key = s_key[i];
-                        if ((key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
+                        const bool c_i = bag ? (s_pos[i] < wlo) : (i < ncand);
+                        if (c_i && (key & mask) == prefix) atomicAdd(&s_hist[(key >> shift) & 255u], 1);
                     }
                     __syncthreads();
                     if (wave == 0) {
@@ -414,6 +451,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                             if (above < rem && rem <= above + cs[k]) {
                                 s_sel[0] = 4 * lane + 3 - k;
                                 s_sel[1] = rem - above;
+                                s_sel[2] = cs[k];      // keys sharing the whole prefix so far
                             }
                             above += cs[k];
                         }
@@ -424,6 +462,78 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     rem = s_sel[1];
                 }
             }
+            if (bag) {
+                // ---- unordered layout: holes below `keep` are filled by kept rows above it ----
+                // A candidate is kept if its key exceeds the threshold, or equals it and is one of
+                // the `rem` earliest tokens among the equals (rank by position, found by a scan
+                // of the candidates only when some equal key has to lose).
+                const int n_eq = (n_global > 0) ? s_sel[2] : 0;
+                int run_h = 0, run_m = 0;
+                const uint64_t lt = (1ull << lane) - 1ull;
+                for (int base = 0; base < m; base += NT) {
+                    const int i = base + tid;
+                    bool kept = false;
+                    if (i < m) {
+                        const int posi = s_pos[i];
+                        if (posi >= wlo) {
+                            kept = true;
+                        } else if (n_global > 0) {
+                            const uint32_t key = s_key[i];
+                            if (key > prefix) {
+                                kept = true;
+                            } else if (key == prefix) {
+                                if (n_eq == rem) {
+                                    kept = true;
+                                } else {
+                                    int rank = 0;
+                                    for (int j = 0; j < m; ++j)
+                                        rank += (s_key[j] == prefix && s_pos[j] < posi) ? 1 : 0;
+                                    kept = rank < rem;
+                                }
+                            }
+                        }
+                    }
+                    const bool hole = (i < keep) && !kept;
+                    const bool mover = (i >= keep) && (i < m) && kept;
+                    const uint64_t hm = __ballot(hole);
+                    const uint64_t mm = __ballot(mover);
+                    if (lane == 0) {
+                        s_wcnt[0][wave] = __popcll(hm);
+                        s_wcnt[1][wave] = __popcll(mm);
+                    }
+                    __syncthreads();
+                    int hr = run_h + __popcll(hm & lt), mr = run_m + __popcll(mm & lt);
+                    int h_all = 0, m_all = 0;
+#pragma unroll
+                    for (int v = 0; v < NW; ++v) {
+                        const int ch = s_wcnt[0][v], cm = s_wcnt[1][v];
+                        if (v < wave) {
+                            hr += ch;
+                            mr += cm;
+                        }
+                        h_all += ch;
+                        m_all += cm;
+                    }
+                    if (i < keep && kept) s_src[i] = (uint16_t)i;
+                    if (hole && hr < a.lds_slots / 2) s_holes[hr] = (uint16_t)i;
+                    if (mover && mr < a.lds_slots / 2) s_movers[mr] = (uint16_t)i;
+                    if (fused && i < m && !kept) {
+                        const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
+                        if (e < kMaxFix) s_evict[e] = i;
+                    }
+                    run_h += h_all;
+                    run_m += m_all;
+                    __syncthreads();
+                }
+                n_moves = run_h < run_m ? run_h : run_m;
+                n_moves = n_moves < a.lds_slots / 2 ? n_moves : a.lds_slots / 2;
+                for (int k = tid; k < run_h; k += NT) {
+                    if (k < a.lds_slots / 2) s_src[s_holes[k]] = (k < n_moves) ? s_movers[k] : s_holes[k];
+                }
+                __syncthreads();
+                if (kout)
+                    for (int j = tid; j < keep; j += NT) kout[j] = s_src[j];
+            } else {
             // Ordered compaction of the kept flags.  A candidate is kept if its key
             // exceeds the threshold, or equals it and is among the first `rem` equals.
             int run_out = 0, run_eq = 0;
@@ -468,7 +578,14 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             }
             if (kout)
                 for (int j = tid; j < keep; j += NT) kout[j] = s_kept[j];
+            }
         }
+
+        // pre-compaction slot of the token that ends up in final slot j
+        auto src_of = [&](int j) -> int {
+            if (bag) return have_list ? (int)s_src[j] : (j == jstar ? len : j);
+            return have_list ? (int)s_kept[j] : j + (j >= jstar ? 1 : 0);
+        };
 
         // ---- output ---------------------------------------------------------------------------
         // kept mass 1 - sum_E p_j decides whether the subtractive form is safe
@@ -498,33 +615,21 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 for (int e = 0; e < EPV; ++e) s_fix[k * D + sub * EPV + e] = pw * f[e];
             }
             __syncthreads();
-            if (tid < LPR) {
-                float Mt = s_redA[0], St = s_wS[0];
-                float at[EPV];
+            // one thread per output element: merge the wave partials relative to the global max
+            for (int e = tid; e < D; e += NT) {
+                float St = 0.f, At = 0.f;
 #pragma unroll
-                for (int e = 0; e < EPV; ++e) at[e] = s_acc[tid * EPV + e];
-                for (int v = 1; v < NW; ++v) {
-                    float a2[EPV];
-#pragma unroll
-                    for (int e = 0; e < EPV; ++e) a2[e] = s_acc[v * D + tid * EPV + e];
-                    merge_acc<EPV>(Mt, St, at, s_redA[v], s_wS[v], a2);
+                for (int v = 0; v < NW; ++v) {
+                    const float r = fast_exp2((s_redA[v] - mx) * kLog2e);   // 0 for an empty wave (-inf)
+                    St = __builtin_fmaf(s_wS[v], r, St);
+                    At = __builtin_fmaf(s_acc[v * D + e], r, At);
                 }
-                float f[EPV];
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    float t = at[e] / St;
-                    for (int k = 0; k < ec; ++k) t -= s_fix[k * D + tid * EPV + e];
-                    f[e] = t / (1.f - pe);
-                }
-                store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
+                float t = At / St;
+                for (int k = 0; k < ec; ++k) t -= s_fix[k * D + e];
+                store_elem<T>(a.out + pair * ROWB, e, t / (1.f - pe));
             }
         } else {
             // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i
-            if (!have_list) {
-                // the E <= 1 paths did not build the list in LDS; do it now
-                for (int j = tid; j < keep; j += NT) s_kept[j] = (uint16_t)(j + (j >= jstar ? 1 : 0));
-                have_list = true;
-            }
             __syncthreads();
 #pragma unroll
             for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
@@ -536,7 +641,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 for (int u = 0; u < UV; ++u) {
                     const int j = j0 + u * NG + grp;
                     if (j < keep) {
-                        int idx = s_kept[j];
+                        int idx = src_of(j);
                         idx = idx < 0 ? 0 : (idx > len ? len : idx);
                         pw[u] = s_p[idx];
                         const char* src = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
@@ -567,32 +672,55 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 if (lane == 0) s_wS[wave] = ps;
             }
             __syncthreads();
-            if (tid < LPR) {
-                float pst = 0.f;
+            for (int e = tid; e < D; e += NT) {
+                float pst = 0.f, t = 0.f;
 #pragma unroll
-                for (int v = 0; v < NW; ++v) pst += s_wS[v];
-                float f[EPV];
-#pragma unroll
-                for (int e = 0; e < EPV; ++e) {
-                    float t = 0.f;
-#pragma unroll
-                    for (int v = 0; v < NW; ++v) t += s_acc[v * D + tid * EPV + e];
-                    f[e] = t / pst;
+                for (int v = 0; v < NW; ++v) {
+                    pst += s_wS[v];
+                    t += s_acc[v * D + e];
                 }
-                store16(a.out + pair * ROWB + tid * 16, pack<T>(f));
+                store_elem<T>(a.out + pair * ROWB, e, t / pst);
             }
         }
 
         // ---- fused compaction: kept rows of K, V, score, pos go to slots 0..keep-1 -----------
         if (fc) {
             __syncthreads();   // s_sc, s_pos and the kept list of every thread are in LDS
-            // final slot j holds the token of pre-compaction slot src(j); src(j) >= j
-            auto src_of = [&](int j) -> int { return have_list ? (int)s_kept[j] : j + (j >= jstar ? 1 : 0); };
+            // final slot j holds the token of pre-compaction slot src(j)
             for (int j = tid; j < keep; j += NT) {
-                const int src = src_of(j);
+                int src = src_of(j);
+                src = src < 0 ? 0 : (src > len ? len : src);
                 Sp[j] = s_sc[src];
                 if (src != j || src == len) Pp[j] = s_pos[src];
             }
+            if (bag) {
+                // Sources (slots >= keep, or the new row) and destinations (holes < keep) are
+                // disjoint, so the rows can move without any ordering.
+                if (!have_list) {
+                    // E <= 1: the only row written is the new one, into the hole or at the end
+                    const int dst = (jstar < len) ? jstar : len;
+                    if (dst < keep) {
+                        if (tid < LPR) {
+                            store16(Kp + (int64_t)dst * ROWB + tid * 16, load16(knew + tid * 16));
+                        } else if (tid < 2 * LPR) {
+                            const int t2 = tid - LPR;
+                            store16(Vp + (int64_t)dst * ROWB + t2 * 16, load16(vnew + t2 * 16));
+                        }
+                    }
+                } else {
+                    for (int k = grp; k < n_moves; k += NG) {
+                        int src = s_movers[k], dst = s_holes[k];
+                        src = src > len ? len : src;
+                        dst = dst >= keep ? keep - 1 : dst;
+                        const char* ks = (src == len) ? knew : Kp + (int64_t)src * ROWB;
+                        const char* vs = (src == len) ? vnew : Vp + (int64_t)src * ROWB;
+                        const Vec16 kr = load16(ks + sub * 16);
+                        const Vec16 vr = load16(vs + sub * 16);
+                        store16(Kp + (int64_t)dst * ROWB + sub * 16, kr);
+                        store16(Vp + (int64_t)dst * ROWB + sub * 16, vr);
+                    }
+                }
+            } else {
             // rows only move down; the prefix with src(j) == j stays (the new row always
             // counts as moved: it comes from k_new / v_new)
             int j0;
@@ -638,6 +766,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                         store16(Vp + (int64_t)dst[u] * ROWB + sub * 16, vv2[u]);
                     }
                 }
+            }
             }
         }
     }
@@ -719,11 +848,13 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.sparsity_bp = p.sparsity_bp;
     a.scale = scale;
     a.fuse_compaction = (p.flags & SWA_FUSE_COMPACTION) ? 1 : 0;
-    a.stash_rows = a.fuse_compaction ? decode_stash_rows(p) : 0;
+    a.unordered = (a.fuse_compaction && (p.flags & SWA_UNORDERED)) ? 1 : 0;
+    a.stash_rows = (a.fuse_compaction && !a.unordered) ? decode_stash_rows(p) : 0;
 
     const int64_t pairs = (int64_t)p.b * p.h;
     const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
-    const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? 16 : 8) + (size_t)a.stash_rows * rowb * 2;
+    const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? (a.unordered ? 20 : 16) : 8) +
+                             (size_t)a.stash_rows * rowb * 2;
     const int nt = decode_block_threads(pairs, bound);
 
     if (p.dtype == SWA_F32) {

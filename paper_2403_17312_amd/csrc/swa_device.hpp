@@ -170,6 +170,25 @@ __device__ __forceinline__ Vec16 pack<BF16>(const float* f)
     return v;
 }
 
+// Round one fp32 value to the cache dtype and store it as element e of a row.
+template <typename T>
+__device__ __forceinline__ void store_elem(char* row, int e, float v);
+template <>
+__device__ __forceinline__ void store_elem<F32>(char* row, int e, float v)
+{
+    reinterpret_cast<float*>(row)[e] = v;
+}
+template <>
+__device__ __forceinline__ void store_elem<F16>(char* row, int e, float v)
+{
+    reinterpret_cast<uint16_t*>(row)[e] = (uint16_t)f32_to_f16_bits(v);
+}
+template <>
+__device__ __forceinline__ void store_elem<BF16>(char* row, int e, float v)
+{
+    reinterpret_cast<uint16_t*>(row)[e] = (uint16_t)f32_to_bf16_bits(v);
+}
+
 __device__ __forceinline__ Vec16 load16(const void* p) { return *reinterpret_cast<const Vec16*>(p); }
 __device__ __forceinline__ void store16(void* p, const Vec16& v) { *reinterpret_cast<Vec16*>(p) = v; }
 
@@ -224,6 +243,37 @@ __device__ __forceinline__ void min64_dpp(uint32_t& hi, uint32_t& lo)
     const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
     hi = take ? h2 : hi;
     lo = take ? l2 : lo;
+}
+// Same, carrying a payload along with the winning key.
+template <int CTRL>
+__device__ __forceinline__ void min64p_dpp(uint32_t& hi, uint32_t& lo, int& pl)
+{
+    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, 0xf, 0xf, true);
+    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, CTRL, 0xf, 0xf, true);
+    const int p2 = __builtin_amdgcn_update_dpp(0, pl, CTRL, 0xf, 0xf, true);
+    const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
+    hi = take ? h2 : hi;
+    lo = take ? l2 : lo;
+    pl = take ? p2 : pl;
+}
+__device__ __forceinline__ void wave_min64p(unsigned long long& v, int& payload)
+{
+    uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
+    min64p_dpp<0xB1>(hi, lo, payload);
+    min64p_dpp<0x4E>(hi, lo, payload);
+    min64p_dpp<0x141>(hi, lo, payload);
+    min64p_dpp<0x140>(hi, lo, payload);
+#pragma unroll
+    for (int o = 16; o <= 32; o <<= 1) {
+        const uint32_t h2 = (uint32_t)__shfl_xor((int)hi, o, kWave);
+        const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, o, kWave);
+        const int p2 = __shfl_xor(payload, o, kWave);
+        const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
+        hi = take ? h2 : hi;
+        lo = take ? l2 : lo;
+        payload = take ? p2 : payload;
+    }
+    v = ((unsigned long long)hi << 32) | lo;
 }
 __device__ __forceinline__ unsigned long long wave_min64(unsigned long long v)
 {

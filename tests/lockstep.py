@@ -80,7 +80,8 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
                  prompt: Optional[dict] = None, verbose: bool = False,
-                 use_len_bound: bool = False, fused: bool = False) -> Report:
+                 use_len_bound: bool = False, fused: bool = False, unordered: bool = False,
+                 sparsity_of_step=None) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
@@ -91,7 +92,11 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
     if fused:
         # swa_decode_step with SWA_FUSE_COMPACTION: one kernel does the step and the compaction
         assert compact_every == 1
-        st.params.flags = B.SWA_FUSE_COMPACTION
+        st.params.flags = B.SWA_FUSE_COMPACTION | (B.SWA_UNORDERED if unordered else 0)
+    else:
+        assert not unordered
+    # Unordered compaction keeps the cache as a set: every GPU tensor is brought into token order
+    # (sorted by pos) before it is compared with the oracle, whose cache is always in token order.
     seqs_t = torch.tensor(seqs, device=device)
     heads_t = torch.tensor(heads, device=device)
 
@@ -120,17 +125,20 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         q, kn, vn = W.make_step(wl, t, prompt["mu"])
         st.seq_len += 1
         n_o = n_o + 1
+        sp_t = wl.sparsity_bp if sparsity_of_step is None else int(sparsity_of_step(t))
+        st.params.sparsity_bp = sp_t          # the budget may change from call to call
         if use_len_bound:
             # exact bound: the longest cache of this step, from the host's replay of the budget
             st.params.len_bound = max(host_len) + 1
         if fused:
             score_prev32 = _sub(st.score, seqs_t, heads_t).cpu().numpy().astype(np.float32)
+            pos_prev = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
             st.decode_compact_step(q, kn, vn)        # swaps cache_len / kept_cnt afterwards
         else:
             st.decode_step(q, kn, vn)
         for s_i in range(wl.b):
             m_i = host_len[s_i] + 1
-            host_len[s_i] = (B.swa_budget(prompt["lengths"][s_i] + t + 1, m_i, wl.w, wl.sparsity_bp)[0]
+            host_len[s_i] = (B.swa_budget(prompt["lengths"][s_i] + t + 1, m_i, wl.w, sp_t)[0]
                              if compact_every > 0 and (t + 1) % compact_every == 0 else m_i)
         do_check = check_steps is None or t in check_steps
         do_compact = compact_every > 0 and (t + 1) % compact_every == 0
@@ -138,7 +146,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         # ---- oracle step from the adopted state ---------------------------------
         q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
         kept_o, cnt_o, out_o, p_o = O.decode_step(q_o, kn_o, vn_o, K_o, V_o, score_o, pos_o, len_o,
-                                                  n_o, wl.w, wl.sparsity_bp, wl.scale)
+                                                  n_o, wl.w, sp_t, wl.scale)
         kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
         if fused:
             # the cache is already compacted: the new lengths are in cache_len (swapped in),
@@ -156,6 +164,30 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                 for hd in range(len(heads)):
                     assert np.array_equal(comp32[i, hd, :c], full32[i, hd, kept_g[i, hd, :c]]), \
                         f"step {t}: compacted importance is not fp32(old + p) of the kept slots"
+            if unordered:
+                # canonical (token-order) views: rank r of the pre-step cache <-> slot order[r]
+                pos_post = _sub(st.pos, seqs_t, heads_t).cpu().numpy()
+                p_can = np.zeros_like(p32)
+                kept_can = np.full_like(kept_g, -1)
+                orders = {}
+                for i, m in enumerate(len_o):
+                    for hd in range(len(heads)):
+                        slot_pos = np.concatenate([pos_prev[i, hd, :m - 1], [n_o[i] - 1]])
+                        order = np.argsort(slot_pos, kind="stable")
+                        assert np.array_equal(slot_pos[order], pos_o[i, hd, :m]), \
+                            f"step {t}: the cached token set differs from the oracle's"
+                        inv = np.empty(m, dtype=np.int64)
+                        inv[order] = np.arange(m)
+                        c = cnt_g[i]
+                        # kept_idx[j] is the pre-compaction slot of the token now in slot j
+                        assert np.array_equal(slot_pos[kept_g[i, hd, :c]], pos_post[i, hd, :c]), \
+                            f"step {t}: kept_idx does not describe the compacted cache"
+                        kept_can[i, hd, :c] = np.sort(inv[kept_g[i, hd, :c]])
+                        p_can[i, hd, :m] = p32[i, hd, order]
+                        full32[i, hd, :m] = full32[i, hd, order]
+                        orders[(i, hd)] = np.argsort(pos_post[i, hd, :c], kind="stable")
+                kept_g = kept_can
+                score_g = full32.astype(np.float64)
         else:
             score_g = _np64(_sub(st.score, seqs_t, heads_t))
             cnt_g = st.kept_cnt[seqs_t].cpu().numpy()
@@ -163,7 +195,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         assert np.array_equal(cnt_g, cnt_o), f"step {t}: kept_cnt {cnt_g} vs {cnt_o}"
 
         if do_check:
-            p_g = _np64(_sub(st.probs, seqs_t, heads_t))
+            p_g = p_can.astype(np.float64) if unordered else _np64(_sub(st.probs, seqs_t, heads_t))
             out_g = _np64(_sub(st.out, seqs_t, heads_t))
             for i, m in enumerate(len_o):
                 pe = np.abs(p_g[i, :, :m] - p_o[i, :, :m])
@@ -177,7 +209,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                 rep.max_score_rel = max(rep.max_score_rel,
                                         float(np.max(se / (np.abs(score_o[i, :, :m]) + 1e-30))))
             # (ii) index sets: oracle selection on the GPU's own fp32 scores, bit-exact
-            kept_ref, cnt_ref = O.select(score_g, len_o, n_o, wl.w, wl.sparsity_bp)
+            kept_ref, cnt_ref = O.select(score_g, len_o, n_o, wl.w, sp_t)
             assert np.array_equal(cnt_ref, cnt_g)
             for i, c in enumerate(cnt_g):
                 assert np.array_equal(kept_g[i, :, :c], kept_ref[i, :, :c]), \
@@ -216,7 +248,12 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                 K_g = _np64(_sub(st.K, seqs_t, heads_t))
                 V_g = _np64(_sub(st.V, seqs_t, heads_t))
                 s_g = _np64(_sub(st.score, seqs_t, heads_t))
-                pos_g = _sub(st.pos, seqs_t, heads_t).cpu().numpy()
+                pos_g = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
+                if unordered:
+                    for (i, hd), o2 in orders.items():
+                        L = len_o[i]
+                        K_g[i, hd, :L], V_g[i, hd, :L] = K_g[i, hd, o2], V_g[i, hd, o2]
+                        s_g[i, hd, :L], pos_g[i, hd, :L] = s_g[i, hd, o2], pos_g[i, hd, o2]
                 for i, L in enumerate(len_o):
                     assert np.array_equal(K_g[i, :, :L], K_o[i, :, :L]), f"step {t}: K after compaction"
                     assert np.array_equal(V_g[i, :, :L], V_o[i, :, :L]), f"step {t}: V after compaction"

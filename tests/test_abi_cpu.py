@@ -44,6 +44,8 @@ def test_params_struct_matches_header(B):
     assert int(re.search(r"#define SWA_MAX_PREFILL_ROWS (\d+)", text).group(1)) == B.SWA_MAX_PREFILL_ROWS
     assert int(re.search(r"#define SWA_MAX_FUSED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_FUSED_SLOTS
     assert int(re.search(r"#define SWA_FUSE_COMPACTION (\d+)", text).group(1)) == B.SWA_FUSE_COMPACTION
+    assert int(re.search(r"#define SWA_UNORDERED (\d+)", text).group(1)) == B.SWA_UNORDERED
+    assert int(re.search(r"#define SWA_MAX_UNORDERED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_UNORDERED_SLOTS
 
 
 def test_strerror_covers_all_codes(B):
@@ -79,7 +81,8 @@ def test_workspace_bytes(B):
     (dict(cap=0), "SWA_ERR_BAD_SHAPE"),
     (dict(cap=16385), "SWA_ERR_CAPACITY"),
     (dict(len_bound=-1), "SWA_ERR_BAD_SHAPE"),
-    (dict(flags=2), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=2), "SWA_ERR_BAD_SHAPE"),          # SWA_UNORDERED needs SWA_FUSE_COMPACTION
+    (dict(flags=4), "SWA_ERR_BAD_SHAPE"),
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
     (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),

@@ -84,6 +84,56 @@ def test_fused_compaction_matches_the_two_call_path(env):
                                steps=9, w=0, sparsity_bp=9000, hh_frac=0.02), fused=True)
 
 
+def test_unordered_compaction_matches_the_oracle_as_a_set(env):
+    # SWA_FUSE_COMPACTION | SWA_UNORDERED: holes are filled instead of shifting rows; the cache is
+    # compared with the oracle after sorting by token position
+    O, B, W, LS = env
+    _say("c1 / c2 lockstep, unordered compaction")
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"], fused=True, unordered=True)
+    assert rep.steps == 16 and rep.evictions > 0
+    LS.run_lockstep(W.CONFIGS["c1_tiny"].replace(prefill_R=8, w=0), fused=True, unordered=True)
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], fused=True, unordered=True, use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+    for dtype, d in [("f32", 128), ("bf16", 64), ("f16", 64), ("bf16", 128)]:
+        wl = W.Workload(f"t_un_{dtype}_{d}", 27, b=3, h=5, d=d, dtype=dtype, prompt_lo=2, prompt_hi=333,
+                        steps=12, w=7, sparsity_bp=7000, hh_frac=0.02, prefill_R=5)
+        LS.run_lockstep(wl, fused=True, unordered=True)
+    LS.run_lockstep(W.Workload("t_un_dense", 28, b=2, h=3, d=128, dtype="f16", prompt_lo=1, prompt_hi=90,
+                               steps=9, w=4, sparsity_bp=0, hh_frac=0.02), fused=True, unordered=True)
+    LS.run_lockstep(W.Workload("t_un_w0", 29, b=2, h=3, d=128, dtype="f16", prompt_lo=50, prompt_hi=90,
+                               steps=9, w=0, sparsity_bp=9000, hh_frac=0.02), fused=True, unordered=True)
+    LS.run_lockstep(W.Workload("t_un_win", 30, b=2, h=3, d=128, dtype="f16", prompt_lo=5, prompt_hi=40,
+                               steps=30, w=16, sparsity_bp=9999, hh_frac=0.02), fused=True, unordered=True)
+
+
+def test_unordered_ties_go_to_the_earliest_token(env):
+    # identical prompt keys => bitwise-equal importance among the old tokens at every step; once the
+    # slots are no longer in token order the tie rule must follow pos, as the oracle's does
+    O, B, W, LS = env
+    for sp, w in [(5000, 3), (3000, 0), (8000, 5)]:
+        wl = W.Workload("t_un_ties", 31, b=2, h=3, d=128, dtype="f16", prompt_lo=40, prompt_hi=70,
+                        steps=25, w=w, sparsity_bp=sp, hh_frac=0.02)
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        for s_i, L in enumerate(prompt["lengths"]):
+            prompt["K"][s_i, :, :L] = prompt["K"][s_i, :, :1].clone()
+        rep = LS.run_lockstep(wl, prompt=prompt, fused=True, unordered=True)
+        assert rep.evictions > 0
+        # a budget that tightens later: many evictions at once on a cache that is out of token
+        # order and full of exact ties (radix select + rank-by-position path)
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        for s_i, L in enumerate(prompt["lengths"]):
+            prompt["K"][s_i, :, :L] = prompt["K"][s_i, :, :1].clone()
+        rep = LS.run_lockstep(wl, prompt=prompt, fused=True, unordered=True,
+                              sparsity_of_step=lambda t: 2000 if t < 12 else (8500 if t < 14 else 6000))
+        assert rep.evictions > 0
+        # the ordered mode on the same inputs (ties by slot) must agree with the oracle as well
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        for s_i, L in enumerate(prompt["lengths"]):
+            prompt["K"][s_i, :, :L] = prompt["K"][s_i, :, :1].clone()
+        LS.run_lockstep(wl, prompt=prompt, fused=True)
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
@@ -93,6 +143,9 @@ def test_c3_opt13b_full_size_sampled_pairs(env):
     _say(f"  {rep}")
     rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero",
                           use_len_bound=True, fused=True)
+    _say(f"  {rep}")
+    rep = LS.run_lockstep(wl, seqs=[0, 1, 17, 31, 32, 63], heads=[0, 7, 20, 39], slack="zero",
+                          use_len_bound=True, fused=True, unordered=True)
     _say(f"  {rep}")
     assert rep.steps == 64
 
@@ -106,6 +159,9 @@ def test_c4_opt30b_full_size_sampled_pairs_with_mfma_prefill(env):
     rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero", use_len_bound=True,
                           fused=True)
     _say(f"  {rep}")
+    rep = LS.run_lockstep(wl, seqs=[0, 13, 31], heads=[0, 28, 55], slack="zero", use_len_bound=True,
+                          fused=True, unordered=True)
+    _say(f"  {rep}")
     assert rep.steps == 128
 
 
@@ -118,7 +174,8 @@ def test_c5_llama7b_full_size_sampled_pairs(env, name):
     _say(f"{name} lockstep (full size, mixed lengths {min(lens)}..{max(lens)}, seqs {seqs})")
     check = set(range(0, 256, 3)) | {1, 2, 254, 255}
     rep = LS.run_lockstep(wl, seqs=seqs, heads=[0, 15, 31], slack="zero", check_steps=check,
-                          use_len_bound=True, fused=(name != "c5_llama7b_sp50"))
+                          use_len_bound=True, fused=(name != "c5_llama7b_sp50"),
+                          unordered=(name == "c5_llama7b_sp80"))
     _say(f"  {rep}")
     assert rep.steps == 256
     torch.cuda.empty_cache()
