@@ -54,8 +54,10 @@ class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
     def __init__(self, B, W, wl, prompt, torch, len_bounds, fused):
-        self.fused = fused
-        flags = B.SWA_FUSE_COMPACTION if fused else 0
+        self.fused = bool(fused)
+        flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
+                 "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED}[fused]
+        self.fused = flags != 0
         params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
         st.K.copy_(prompt["K"])
@@ -290,8 +292,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default="c2_opt6p7b")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
-    ap.add_argument("--step-mode", choices=["fused", "split"], default="fused",
-                    help="fused: one kernel per step; split: swa_decode_step + swa_compact_kv")
+    ap.add_argument("--step-mode", choices=["unordered", "fused", "split"], default="unordered",
+                    help="fused: one kernel per step, cache kept in token order; unordered: one kernel per "
+                         "step, compaction fills holes (SWA_UNORDERED); split: swa_decode_step + swa_compact_kv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -314,7 +317,7 @@ def main():
     wl = W.CONFIGS[args.config]
     steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
     warmup = args.warmup if args.warmup is not None else wl.steps
-    fused = args.step_mode == "fused"
+    fused = args.step_mode if args.step_mode != "split" else False
     res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused)
 
     # Average launch duration of the dominant kernel.  Fused mode: the step IS one kernel, so the
@@ -335,8 +338,11 @@ def main():
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
                    "replicas": res["replicas"], "launch": args.mode,
-                   "step": ("swa_decode_step with SWA_FUSE_COMPACTION (one kernel, kept_idx not requested)"
-                            if fused else "swa_decode_step + swa_compact_kv")},
+                   "step": {"unordered": "swa_decode_step with SWA_FUSE_COMPACTION|SWA_UNORDERED (one kernel, "
+                                         "hole-filling compaction, kept_idx not requested)",
+                            "fused": "swa_decode_step with SWA_FUSE_COMPACTION (one kernel, token-ordered "
+                                     "compaction, kept_idx not requested)",
+                            "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]},
         "roofline": {
             "bound": "hbm", "kernel": "swa_decode_kernel",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
