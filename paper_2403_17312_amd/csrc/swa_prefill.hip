@@ -80,13 +80,13 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     constexpr int NT = 256;
     constexpr int NW = NT / kWave;
     constexpr int ROWB = D * Elem<T>::kBytes;
-    constexpr int NV = (ROWB / 2) / 16;   // 16-byte vectors per half-row
+    constexpr int NV = (ROWB / 2) / 16;   // 16-byte vectors per lane and tile row
     constexpr int RP = RT * 32;           // padded query rows
 
     __shared__ float s_m[NW][RP];
     __shared__ float s_l[NW][RP];
-    __shared__ float s_M[RP];
-    __shared__ float s_invL[RP];
+    __shared__ __align__(16) float s_M[RP];
+    __shared__ __align__(16) float s_invL[RP];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -108,6 +108,11 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     const char* Kp = a.k_cache + pair * (int64_t)cap * ROWB;
     const char* Qp = a.q_tail + pair * (int64_t)R * ROWB;
 
+    // Lane (row, hb) supplies the 16-byte chunks 2v + hb, v = 0..NV-1, of its row: the two
+    // half-wave lanes of a row read adjacent chunks, and query and key fragments use the same
+    // walk, so every MFMA issue contracts matching slices of the head dimension.
+    const int lane_off = hb * 16;
+
     // Query fragments stay in registers for both passes.  Rows >= R are zero.
     Vec16 qv[RT][NV];
 #pragma unroll
@@ -115,13 +120,23 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
         const int r = rt * 32 + l32;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            qv[rt][v] = (r < R) ? load16(Qp + (int64_t)r * ROWB + hb * (ROWB / 2) + v * 16)
+            qv[rt][v] = (r < R) ? load16(Qp + (int64_t)r * ROWB + v * 32 + lane_off)
                                 : Vec16{0u, 0u, 0u, 0u};
         }
     }
 
     const int ntiles = (s + 31) / 32;
     const int t_off = s - R;   // query r sits at position t_off + r and sees keys 0..t_off+r
+
+    // Unconditional tile load (rows past the end re-read the last row and are masked later), so
+    // that the loads of the next tile can stay in flight while the current one is reduced.
+    auto load_tile = [&](int tile, Vec16(&kv)[NV]) {
+        int krow = tile * 32 + l32;
+        krow = krow < s ? krow : s - 1;
+        const char* src = Kp + (int64_t)krow * ROWB + lane_off;
+#pragma unroll
+        for (int v = 0; v < NV; ++v) kv[v] = load16(src + v * 32);
+    };
 
     // ------------------------------ pass 1: row statistics ------------------------------
     float M[RT], L[RT];
@@ -130,12 +145,7 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
         M[rt] = -INFINITY;
         L[rt] = 0.f;
     }
-    for (int tile = wave; tile < ntiles; tile += NW) {
-        int krow = tile * 32 + l32;
-        krow = krow < s ? krow : s - 1;   // clamped rows are masked below
-        Vec16 kv[NV];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) kv[v] = load16(Kp + (int64_t)krow * ROWB + hb * (ROWB / 2) + v * 16);
+    auto stats_tile = [&](int tile, const Vec16(&kv)[NV]) {
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
             float16_t c;
@@ -155,12 +165,22 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
             }
             if (mx > -INFINITY) {
                 const float Mn = fmaxf(M[rt], mx);
-                float acc = (M[rt] == -INFINITY) ? 0.f : L[rt] * exp2f(M[rt] - Mn);
+                float acc = L[rt] * __builtin_amdgcn_exp2f(M[rt] - Mn);   // 0 while M is -inf
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc += exp2f(z[i] - Mn);
+                for (int i = 0; i < 16; ++i) acc += __builtin_amdgcn_exp2f(z[i] - Mn);
                 M[rt] = Mn;
                 L[rt] = acc;
             }
+        }
+    };
+    {
+        Vec16 kA[NV], kB[NV];
+        load_tile(wave, kA);
+        for (int tile = wave; tile < ntiles; tile += 2 * NW) {
+            load_tile(tile + NW, kB);
+            stats_tile(tile, kA);
+            load_tile(tile + 2 * NW, kA);
+            if (tile + NW < ntiles) stats_tile(tile + NW, kB);
         }
     }
 #pragma unroll
@@ -185,12 +205,8 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     __syncthreads();
 
     // ------------------------------ pass 2: column sums ---------------------------------
-    for (int tile = wave; tile < ntiles; tile += NW) {
+    auto colsum_tile = [&](int tile, const Vec16(&kv)[NV]) {
         const int key = tile * 32 + l32;
-        const int krow = key < s ? key : s - 1;
-        Vec16 kv[NV];
-#pragma unroll
-        for (int v = 0; v < NV; ++v) kv[v] = load16(Kp + (int64_t)krow * ROWB + hb * (ROWB / 2) + v * 16);
         float colsum = 0.f;
 #pragma unroll
         for (int rt = 0; rt < RT; ++rt) {
@@ -200,15 +216,32 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
 #pragma unroll
             for (int v = 0; v < NV; ++v) c = Mfma<T>::run(qv[rt][v], kv[v], c);   // C[query][key]
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int r = rt * 32 + 8 * (i / 4) + 4 * hb + (i % 4);
-                const bool vis = (r < R) && (key <= t_off + r);
-                const float p = exp2f(c[i] * a.scale_log2e - s_M[r]) * s_invL[r];
-                colsum += vis ? p : 0.f;
+            for (int g = 0; g < 4; ++g) {
+                // the lane's rows 8g + 4hb .. +3 of this query tile: one 16-byte LDS read each
+                const int r0 = rt * 32 + 8 * g + 4 * hb;
+                const float4_t Mr = *reinterpret_cast<const float4_t*>(&s_M[r0]);
+                const float4_t Ir = *reinterpret_cast<const float4_t*>(&s_invL[r0]);
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int r = r0 + j;
+                    const bool vis = (r < R) && (key <= t_off + r);
+                    const float p = __builtin_amdgcn_exp2f(c[4 * g + j] * a.scale_log2e - Mr[j]) * Ir[j];
+                    colsum += vis ? p : 0.f;
+                }
             }
         }
         colsum += __shfl_xor(colsum, 32, kWave);
         if (hb == 0 && key < s) Sp[key] = colsum;
+    };
+    {
+        Vec16 kA[NV], kB[NV];
+        load_tile(wave, kA);
+        for (int tile = wave; tile < ntiles; tile += 2 * NW) {
+            load_tile(tile + NW, kB);
+            colsum_tile(tile, kA);
+            load_tile(tile + 2 * NW, kA);
+            if (tile + NW < ntiles) colsum_tile(tile + NW, kB);
+        }
     }
     for (int j = s + tid; j < cap; j += NT) Sp[j] = 0.f;
 }
