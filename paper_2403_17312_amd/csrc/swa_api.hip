@@ -56,10 +56,11 @@ int decode_block_threads(int64_t pairs, int len_bound)
         return (v == 64 || v == 128 || v == 256 || v == 512) ? v : 0;
     }();
     if (forced) return forced;
-    // Measured on MI355X (all five workloads): long caches want 512 threads per pair, the
-    // short caches of the steady state 256; the pair count matters little.
+    // Measured on MI355X (all five workloads): caches of a thousand slots and more (the first
+    // step after a prompt, low sparsity) want 512 threads per pair, shorter ones 256; the pair
+    // count matters little.
     (void)pairs;
-    return len_bound > 400 ? 512 : 256;
+    return len_bound >= 1024 ? 512 : 256;
 }
 
 __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)
