@@ -40,6 +40,7 @@ extern "C" {
 
 #define SWA_MAX_CAP 16384 /* slots per (sequence, head); bounded by LDS per workgroup */
 #define SWA_MAX_PREFILL_ROWS 128
+#define SWA_W_EVEN_SPLIT (-1)
 
 typedef enum { SWA_F32 = 0, SWA_F16 = 1, SWA_BF16 = 2 } swa_dtype;
 
@@ -60,7 +61,9 @@ typedef struct {
     int32_t h;           /* heads */
     int32_t d;           /* head dimension, 64 or 128 */
     int32_t cap;         /* slots per (sequence, head) in every cache tensor */
-    int32_t w;           /* local window: the most recent w tokens are always kept (>= 0) */
+    int32_t w;           /* local window: the most recent w tokens are always kept (>= 0), or
+                            SWA_W_EVEN_SPLIT for Algorithm 1's own rule, w = nint(n*r/2) per
+                            sequence with as many globally dynamic tokens */
     int32_t sparsity_bp; /* KV sparsity in basis points, 0..9999; caching ratio r = 1 - sparsity */
     int32_t dtype;       /* swa_dtype of q, k_new, v_new, caches, out */
     float scale;         /* logit scale; 0 selects 1/sqrt(d) (Eq. 1) */
@@ -125,7 +128,8 @@ int swa_check_status(const swa_params *params, void *workspace, void *stream, in
  *   keep_raw = nearest integer of n * (1 - sparsity)   (halves round up)
  *   n_local  = min(w, m)
  *   keep     = min(m, max(keep_raw, n_local)),  n_global = keep - n_local.
- * Algorithm 1's even split is the case w = nearest integer of n*r/2.
+ * w = SWA_W_EVEN_SPLIT is Algorithm 1 line 1 itself: k = nearest integer of n*r/2 (halves
+ * round up), w = k and keep_raw = 2k.
  */
 int swa_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp, int32_t *keep,
                int32_t *n_local, int32_t *n_global);

@@ -80,11 +80,19 @@ void swa_oracle_set_num_threads(int t)
 /*   keep     = min(m, max(keep_raw, n_local))                              */
 /*   n_global = keep - n_local                                              */
 /* n is the logical sequence length, m the number of slots in the cache.    */
+/* w < 0 selects Algorithm 1's own even split: k = nearest integer of      */
+/* n*r/2 locally static tokens and as many globally dynamic ones, i.e.     */
+/* w = k and keep_raw = 2k.                                                 */
 /* ------------------------------------------------------------------------ */
 void swa_oracle_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp,
                        int32_t *keep, int32_t *n_local, int32_t *n_global)
 {
     int64_t keep_raw = ((int64_t)n * (int64_t)(10000 - sparsity_bp) + 5000) / 10000;
+    if (w < 0) {
+        int64_t k = ((int64_t)n * (int64_t)(10000 - sparsity_bp) + 10000) / 20000;
+        w = (int32_t)k;
+        keep_raw = 2 * k;
+    }
     int64_t wl = w < m ? w : m;
     int64_t k = keep_raw > wl ? keep_raw : wl;
     if (k > m) k = m;

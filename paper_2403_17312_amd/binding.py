@@ -22,6 +22,7 @@ SWA_ERR_NULL, SWA_ERR_BAD_SHAPE, SWA_ERR_UNSUPPORTED_D, SWA_ERR_UNSUPPORTED_DTYP
 SWA_ERR_BAD_SPARSITY, SWA_ERR_CAPACITY, SWA_ERR_HIP, SWA_ERR_ALIGNMENT = -5, -6, -7, -8
 SWA_MAX_CAP = 16384
 SWA_MAX_PREFILL_ROWS = 128
+SWA_W_EVEN_SPLIT = -1
 SWA_FUSE_COMPACTION = 1
 SWA_MAX_FUSED_SLOTS = 9216
 SWA_UNORDERED = 2

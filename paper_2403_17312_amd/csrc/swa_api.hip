@@ -36,7 +36,7 @@ int decode_stash_rows(const swa_params& p)
         const char* e = getenv("SWA_STASH_ROWS");   // tuning override, multiple of 16 in 0..96
         return e ? atoi(e) : -1;
     }();
-    int rows = ((p.w + 16 + 15) / 16) * 16;
+    int rows = p.w < 0 ? 48 : ((p.w + 16 + 15) / 16) * 16;
     if (rows > 96) rows = 96;
     if (forced >= 0 && forced <= 96) rows = (forced / 16) * 16;
     const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
@@ -82,7 +82,7 @@ static int validate(const swa_params* p)
     if (!p) return SWA_ERR_NULL;
     if (p->dtype != SWA_F32 && p->dtype != SWA_F16 && p->dtype != SWA_BF16) return SWA_ERR_UNSUPPORTED_DTYPE;
     if (p->d != 64 && p->d != 128) return SWA_ERR_UNSUPPORTED_D;
-    if (p->b < 1 || p->h < 1 || p->cap < 1 || p->w < 0) return SWA_ERR_BAD_SHAPE;
+    if (p->b < 1 || p->h < 1 || p->cap < 1 || p->w < SWA_W_EVEN_SPLIT) return SWA_ERR_BAD_SHAPE;
     if ((int64_t)p->b * p->h > 0x7fffffffLL) return SWA_ERR_BAD_SHAPE;
     if (p->cap > SWA_MAX_CAP) return SWA_ERR_CAPACITY;
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
@@ -131,9 +131,10 @@ int swa_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp, int32_t* ke
                int32_t* n_global)
 {
     if (!keep || !n_local || !n_global) return SWA_ERR_NULL;
-    if (n < 0 || m < 0 || w < 0) return SWA_ERR_BAD_SHAPE;
+    if (n < 0 || m < 0 || w < SWA_W_EVEN_SPLIT) return SWA_ERR_BAD_SHAPE;
     if (sparsity_bp < 0 || sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
-    swa::budget(n, m, w, sparsity_bp, *keep, *n_local, *n_global);
+    int32_t w_eff = 0;
+    swa::budget(n, m, w, sparsity_bp, *keep, *n_local, *n_global, w_eff);
     return SWA_OK;
 }
 

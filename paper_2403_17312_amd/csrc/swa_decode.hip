@@ -152,9 +152,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         const char* knew = a.k_new + pair * ROWB;
         const char* vnew = a.v_new + pair * ROWB;
 
-        budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global);
+        int w_eff = 0;
+        budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global, w_eff);
         const int ncand = m - n_local;
-        const int wlo = n - a.w;                      // unordered layout: the window is pos >= wlo
+        const int wlo = n - w_eff;                    // unordered layout: the window is pos >= wlo
         const int E = m - keep;                       // evictions of this step
         const bool fused = (E <= kMaxFix) && (8 * E <= m);
         // first stashed slot (m = nothing stashed: only the streaming schedule fills the stash)

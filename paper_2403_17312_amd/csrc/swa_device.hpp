@@ -325,10 +325,19 @@ __device__ __forceinline__ float block_max(float v, float* red)
 
 // Budget of Algorithm 1 line 1 with an independent window (integer arithmetic on
 // basis points so that host and device agree exactly).
+// w < 0: Algorithm 1's even split, k = nint(n*r/2) local and k global tokens.  w_eff returns the
+// window actually used.
 __host__ __device__ __forceinline__ void budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp,
-                                                int32_t& keep, int32_t& n_local, int32_t& n_global)
+                                                int32_t& keep, int32_t& n_local, int32_t& n_global,
+                                                int32_t& w_eff)
 {
     long long keep_raw = ((long long)n * (long long)(10000 - sparsity_bp) + 5000) / 10000;
+    if (w < 0) {
+        const long long k = ((long long)n * (long long)(10000 - sparsity_bp) + 10000) / 20000;
+        w = (int32_t)k;
+        keep_raw = 2 * k;
+    }
+    w_eff = w;
     long long wl = w < m ? w : m;
     long long k = keep_raw > wl ? keep_raw : wl;
     if (k > m) k = m;

@@ -220,7 +220,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                     diff = a ^ b_
                     if diff:
                         m = len_o[i]
-                        nl = min(wl.w, m)
+                        nl = O.budget(int(n_o[i]), int(m), wl.w, sp_t)[1]
                         cand = np.sort(score_o[i, hd, :m - nl])[::-1]
                         cutoff = cand[c - nl - 1]
                         for j in diff:

@@ -64,6 +64,10 @@ def test_budget_helper_matches_hand_worked_values(B):
     assert B.swa_budget(100, 5, 64, 9000) == (5, 5, 0)
     with pytest.raises(B.SwaError):
         B.swa_budget(10, 10, 1, 10000)
+    rows = [l.split() for l in open(os.path.join(ROOT, "tests", "golden", "even_split.txt"))
+            if l[0] != "#"]
+    for n, sp, _, k in rows:
+        assert B.swa_budget(int(n), int(n), B.SWA_W_EVEN_SPLIT, int(sp) * 100) == (2 * int(k), int(k), int(k))
 
 
 def test_workspace_bytes(B):
@@ -77,7 +81,7 @@ def test_workspace_bytes(B):
     (dict(d=96), "SWA_ERR_UNSUPPORTED_D"),
     (dict(dtype=7), "SWA_ERR_UNSUPPORTED_DTYPE"),
     (dict(b=0), "SWA_ERR_BAD_SHAPE"),
-    (dict(w=-1), "SWA_ERR_BAD_SHAPE"),
+    (dict(w=-2), "SWA_ERR_BAD_SHAPE"),
     (dict(cap=0), "SWA_ERR_BAD_SHAPE"),
     (dict(cap=16385), "SWA_ERR_CAPACITY"),
     (dict(len_bound=-1), "SWA_ERR_BAD_SHAPE"),

@@ -134,6 +134,22 @@ def test_unordered_ties_go_to_the_earliest_token(env):
         LS.run_lockstep(wl, prompt=prompt, fused=True)
 
 
+def test_even_split_of_algorithm_1_in_every_step_mode(env):
+    # w = SWA_W_EVEN_SPLIT: k = nint(n r / 2) local and k global tokens, recomputed per sequence and step
+    O, B, W, LS = env
+    for sp in (8000, 5000):
+        wl = W.Workload("t_even", 33, b=4, h=3, d=128, dtype="f16", prompt_lo=30, prompt_hi=400,
+                        steps=14, w=B.SWA_W_EVEN_SPLIT, sparsity_bp=sp, hh_frac=0.02, prefill_R=4)
+        _say(f"even split sp={sp}")
+        r0 = LS.run_lockstep(wl)
+        r1 = LS.run_lockstep(wl, fused=True)
+        r2 = LS.run_lockstep(wl, fused=True, unordered=True)
+        assert r0.evictions == r1.evictions == r2.evictions > 0
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"].replace(w=B.SWA_W_EVEN_SPLIT), fused=True, unordered=True,
+                          use_len_bound=True)
+    assert rep.steps == 32
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]

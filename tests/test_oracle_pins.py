@@ -58,6 +58,31 @@ def test_budget_clamps(oracle):
     assert oracle.budget(7, 7, 2, 0) == (7, 2, 5)                # sparsity 0 keeps all
 
 
+def test_even_split_budget_matches_hand_worked_values(oracle):
+    # Algorithm 1 line 1 itself: k = nint(n r / 2) locally static and k globally dynamic tokens
+    rows = [l.split() for l in open(os.path.join(GOLDEN, "even_split.txt")) if l[0] != "#"]
+    assert len(rows) >= 6
+    for n, sp, _, k in rows:
+        n, sp, k = int(n), int(sp), int(k)
+        assert oracle.budget(n, n, -1, sp * 100) == (2 * k, k, k), (n, sp)
+    # clamps: never more than what is cached
+    assert oracle.budget(1000, 30, -1, 8000) == (30, 30, 0)
+    assert oracle.budget(1000, 150, -1, 8000) == (150, 100, 50)
+
+
+def test_even_split_selection_keeps_k_local_and_k_global(oracle):
+    rng = np.random.default_rng(21)
+    n = 40
+    score = rng.random((1, 2, 48))
+    cl = np.array([n], dtype=np.int32)
+    kept_idx, kept_cnt = oracle.select(score, cl, cl, -1, 6000)      # r = 0.4: k = 8
+    assert kept_cnt[0] == 16
+    for hd in range(2):
+        lst = kept_idx[0, hd, :16].tolist()
+        assert lst[8:] == list(range(32, 40))
+        assert lst[:8] == sorted(np.argsort(-score[0, hd, :32], kind="stable")[:8].tolist())
+
+
 def test_even_split_mode_of_algorithm_1(oracle):
     # Alg. 1 line 1: k = nint(n r / 2) local and as many global tokens.  With
     # w = k and a budget of 2k the generalised rule gives exactly that split.
