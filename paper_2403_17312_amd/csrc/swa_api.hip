@@ -49,11 +49,11 @@ int decode_stash_rows(const swa_params& p)
 
 int decode_block_threads(int64_t pairs, int len_bound)
 {
-    // Tuning override (64, 128, 256 or 512), read once.
+    // Tuning override (128, 256 or 512), read once.
     static const int forced = [] {
         const char* e = getenv("SWA_DECODE_NT");
         const int v = e ? atoi(e) : 0;
-        return (v == 64 || v == 128 || v == 256 || v == 512) ? v : 0;
+        return (v == 128 || v == 256 || v == 512) ? v : 0;
     }();
     if (forced) return forced;
     // Measured on MI355X (all five workloads): caches of a thousand slots and more (the first

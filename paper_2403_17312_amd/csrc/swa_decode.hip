@@ -813,7 +813,6 @@ template <typename T, int D>
 static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, int nt, hipStream_t stream)
 {
     switch (nt) {
-        case 64: return launch_decode_nt<T, D, 64>(a, pairs, lds_bytes, stream);
         case 128: return launch_decode_nt<T, D, 128>(a, pairs, lds_bytes, stream);
         case 256: return launch_decode_nt<T, D, 256>(a, pairs, lds_bytes, stream);
         default: return launch_decode_nt<T, D, 512>(a, pairs, lds_bytes, stream);

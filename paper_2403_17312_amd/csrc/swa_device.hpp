@@ -234,17 +234,7 @@ __device__ __forceinline__ float wave_max(float v)
     v = fmaxf(v, __shfl_xor(v, 32, kWave));
     return v;
 }
-// Minimum of a 64-bit key held as (hi, lo), lexicographic.
-template <int CTRL>
-__device__ __forceinline__ void min64_dpp(uint32_t& hi, uint32_t& lo)
-{
-    const uint32_t h2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)hi, CTRL, 0xf, 0xf, true);
-    const uint32_t l2 = (uint32_t)__builtin_amdgcn_update_dpp(0, (int)lo, CTRL, 0xf, 0xf, true);
-    const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
-    hi = take ? h2 : hi;
-    lo = take ? l2 : lo;
-}
-// Same, carrying a payload along with the winning key.
+// Lexicographic minimum of a 64-bit key held as (hi, lo), carrying a payload along with the winner.
 template <int CTRL>
 __device__ __forceinline__ void min64p_dpp(uint32_t& hi, uint32_t& lo, int& pl)
 {
@@ -275,54 +265,6 @@ __device__ __forceinline__ void wave_min64p(unsigned long long& v, int& payload)
     }
     v = ((unsigned long long)hi << 32) | lo;
 }
-__device__ __forceinline__ unsigned long long wave_min64(unsigned long long v)
-{
-    uint32_t hi = (uint32_t)(v >> 32), lo = (uint32_t)v;
-    min64_dpp<0xB1>(hi, lo);
-    min64_dpp<0x4E>(hi, lo);
-    min64_dpp<0x141>(hi, lo);
-    min64_dpp<0x140>(hi, lo);
-#pragma unroll
-    for (int o = 16; o <= 32; o <<= 1) {
-        const uint32_t h2 = (uint32_t)__shfl_xor((int)hi, o, kWave);
-        const uint32_t l2 = (uint32_t)__shfl_xor((int)lo, o, kWave);
-        const bool take = (h2 < hi) || (h2 == hi && l2 < lo);
-        hi = take ? h2 : hi;
-        lo = take ? l2 : lo;
-    }
-    return ((unsigned long long)hi << 32) | lo;
-}
-
-// All threads get the result.  `red` is an LDS array of at least blockDim.x/64 floats.
-// Two barriers; `red` may be reused right after the call returns... by a later
-// call of these helpers only (each call starts with a barrier-protected write).
-template <int NT>
-__device__ __forceinline__ float block_sum(float v, float* red)
-{
-    constexpr int NW = NT / kWave;
-    v = wave_sum(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float t = 0.f;
-#pragma unroll
-    for (int i = 0; i < NW; ++i) t += red[i];
-    return t;
-}
-template <int NT>
-__device__ __forceinline__ float block_max(float v, float* red)
-{
-    constexpr int NW = NT / kWave;
-    v = wave_max(v);
-    __syncthreads();
-    if ((threadIdx.x & 63) == 0) red[threadIdx.x >> 6] = v;
-    __syncthreads();
-    float t = red[0];
-#pragma unroll
-    for (int i = 1; i < NW; ++i) t = fmaxf(t, red[i]);
-    return t;
-}
-
 // Budget of Algorithm 1 line 1 with an independent window (integer arithmetic on
 // basis points so that host and device agree exactly).
 // w < 0: Algorithm 1's even split, k = nint(n*r/2) local and k global tokens.  w_eff returns the
