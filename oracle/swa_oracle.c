@@ -39,7 +39,9 @@
  *     with the sum of the last R prompt rows (Alg. 1 line 2) and increased by
  *     the current row at every decode step;
  *   - global candidates exclude the local window, selection is per
- *     (sequence, head), ties go to the lowest slot;
+ *     (sequence, head) -- or, on request, per sequence from the local
+ *     attention sum reduced over the heads, as Algorithm 1's header notes --
+ *     and ties go to the lowest slot;
  *   - the kept list is in ascending slot order and compaction preserves it.
  */
 #include <math.h>
@@ -244,6 +246,38 @@ int swa_oracle_select(int32_t b, int32_t h, int32_t cap, int32_t w, int32_t spar
 }
 
 /* ------------------------------------------------------------------------ */
+/* Selection with the local attention sum reduced along the head dimension   */
+/* (the note in Algorithm 1's header): S_i = sum over heads of score[s,hd,i], */
+/* one selection per sequence, every head of the sequence gets the same list. */
+/* ------------------------------------------------------------------------ */
+int swa_oracle_select_shared(int32_t b, int32_t h, int32_t cap, int32_t w, int32_t sparsity_bp,
+                             const double *score, const int32_t *cache_len, const int32_t *seq_len,
+                             int32_t *kept_idx, int32_t *kept_cnt)
+{
+    double *summed = (double *)malloc(sizeof(double) * (size_t)b * cap);
+    int32_t *one = (int32_t *)malloc(sizeof(int32_t) * (size_t)b * cap);
+    if (!summed || !one) {
+        free(summed);
+        free(one);
+        return SWA_ORACLE_ERR_ALLOC;
+    }
+    for (int32_t s = 0; s < b; ++s)
+        for (int32_t i = 0; i < cap; ++i) {
+            double t = 0.0;
+            for (int32_t hd = 0; hd < h; ++hd) t += score[((size_t)s * h + hd) * cap + i];
+            summed[(size_t)s * cap + i] = t;
+        }
+    int rc = swa_oracle_select(b, 1, cap, w, sparsity_bp, summed, cache_len, seq_len, one, kept_cnt);
+    if (rc == SWA_ORACLE_OK)
+        for (int32_t s = 0; s < b; ++s)
+            for (int32_t hd = 0; hd < h; ++hd)
+                memcpy(kept_idx + ((size_t)s * h + hd) * cap, one + (size_t)s * cap, sizeof(int32_t) * (size_t)cap);
+    free(summed);
+    free(one);
+    return rc;
+}
+
+/* ------------------------------------------------------------------------ */
 /* Sparse attention (Alg. 1 lines 6-8): gather K_s, V_s by the kept list,    */
 /* AW = softmax(q K_s^T * scale), Attn = AW V_s.                              */
 /* ------------------------------------------------------------------------ */
@@ -344,14 +378,16 @@ int swa_oracle_compact(int32_t b, int32_t h, int32_t d, int32_t cap,
 /* One decode step, in the order the method is stated for this build:        */
 /* append -> attention weights over the whole cache -> importance            */
 /* accumulation -> budget + selection -> sparse attention over the kept set. */
-/* probs may be NULL.                                                         */
+/* probs may be NULL.  head_shared != 0 selects one token set per sequence   */
+/* from the head-summed local attention sum.                                  */
 /* ------------------------------------------------------------------------ */
 int swa_oracle_decode_step(int32_t b, int32_t h, int32_t d, int32_t cap, int32_t w,
                            int32_t sparsity_bp, double scale,
                            const double *q, const double *k_new, const double *v_new,
                            double *K, double *V, double *score, int32_t *pos,
                            int32_t *cache_len, const int32_t *seq_len,
-                           int32_t *kept_idx, int32_t *kept_cnt, double *out, double *probs)
+                           int32_t *kept_idx, int32_t *kept_cnt, double *out, double *probs,
+                           int32_t head_shared)
 {
     int rc = swa_oracle_append(b, h, d, cap, k_new, v_new, K, V, score, pos, cache_len, seq_len);
     if (rc) return rc;
@@ -363,7 +399,9 @@ int swa_oracle_decode_step(int32_t b, int32_t h, int32_t d, int32_t cap, int32_t
     swa_oracle_probs(b, h, d, cap, scale, q, K, cache_len, p);
     swa_oracle_accumulate(b, h, cap, p, cache_len, score);
     if (!probs) free(p);
-    rc = swa_oracle_select(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt);
+    rc = head_shared
+             ? swa_oracle_select_shared(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt)
+             : swa_oracle_select(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt);
     if (rc) return rc;
     return swa_oracle_sparse_attention(b, h, d, cap, scale, q, K, V, kept_idx, kept_cnt, out);
 }

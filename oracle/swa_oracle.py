@@ -110,13 +110,14 @@ def accumulate(p, cache_len, score) -> None:
                                 _pi(_i32(cache_len)), _pd(score))
 
 
-def select(score, cache_len, seq_len, w: int, sparsity_bp: int):
+def select(score, cache_len, seq_len, w: int, sparsity_bp: int, head_shared: bool = False):
     """Returns (kept_idx [b,h,cap] padded with -1, kept_cnt [b])."""
     score = _f64(score)
     b, h, cap = score.shape
     kept_idx = np.full((b, h, cap), -1, dtype=np.int32)
     kept_cnt = np.zeros((b,), dtype=np.int32)
-    rc = lib().swa_oracle_select(ctypes.c_int32(b), ctypes.c_int32(h), ctypes.c_int32(cap),
+    fn = lib().swa_oracle_select_shared if head_shared else lib().swa_oracle_select
+    rc = fn(ctypes.c_int32(b), ctypes.c_int32(h), ctypes.c_int32(cap),
                                  ctypes.c_int32(w), ctypes.c_int32(sparsity_bp), _pd(score),
                                  _pi(_i32(cache_len)), _pi(_i32(seq_len)), _pi(kept_idx),
                                  _pi(kept_cnt))
@@ -143,7 +144,7 @@ def compact(K, V, score, pos, kept_idx, kept_cnt, cache_len) -> None:
 
 
 def decode_step(q, k_new, v_new, K, V, score, pos, cache_len, seq_len, w: int, sparsity_bp: int,
-                scale: float, want_probs: bool = True):
+                scale: float, want_probs: bool = True, head_shared: bool = False):
     """One full step.  In place: K, V, score, pos, cache_len.
 
     Returns (kept_idx, kept_cnt, out, probs or None).
@@ -157,7 +158,7 @@ def decode_step(q, k_new, v_new, K, V, score, pos, cache_len, seq_len, w: int, s
         b, h, d, cap, ctypes.c_int32(w), ctypes.c_int32(sparsity_bp), ctypes.c_double(scale),
         _pd(_f64(q)), _pd(_f64(k_new)), _pd(_f64(v_new)), _pd(K), _pd(V), _pd(score), _pi(pos),
         _pi(cache_len), _pi(_i32(seq_len)), _pi(kept_idx), _pi(kept_cnt), _pd(out),
-        _pd(p) if want_probs else None)
+        _pd(p) if want_probs else None, ctypes.c_int32(1 if head_shared else 0))
     _check(rc, "decode_step")
     return kept_idx, kept_cnt, out, p
 

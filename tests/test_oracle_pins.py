@@ -374,6 +374,35 @@ def test_permuting_candidates_permutes_selection_not_output(oracle):
     np.testing.assert_allclose(o1, o2, rtol=1e-12)
 
 
+def test_head_shared_selection(oracle):
+    # the local attention sum reduced over the heads: one token set per sequence
+    rng = np.random.default_rng(22)
+    b, h, cap = 3, 4, 40
+    lens = np.array([40, 17, 9], dtype=np.int32)
+    score = rng.integers(0, 6, size=(b, h, cap)).astype(np.float64) / 4.0     # dyadic: exact sums, many ties
+    for w, sp in [(3, 6000), (0, 5000), (5, 9000)]:
+        kept, cnt = oracle.select(score, lens, lens, w, sp, head_shared=True)
+        # every head of a sequence gets the same list ...
+        for hd in range(1, h):
+            np.testing.assert_array_equal(kept[:, hd], kept[:, 0])
+        # ... which is the per-head rule applied to the head-summed importance (numpy sum, h = 1)
+        ref, cnt1 = oracle.select(score.sum(axis=1, keepdims=True), lens, lens, w, sp)
+        np.testing.assert_array_equal(cnt, cnt1)
+        np.testing.assert_array_equal(kept[:, 0], ref[:, 0])
+        # brute force on the shortest sequence
+        keep, nl, ng = oracle.budget(9, 9, w, sp)
+        tot = score[2].sum(axis=0)
+        expect = _brute_force_topk(list(tot[:9 - nl]), ng) + list(range(9 - nl, 9))
+        assert kept[2, 0, :keep].tolist() == expect
+    # with one head it is the ordinary selection, and head order does not matter
+    k1, _ = oracle.select(score[:, :1], lens, lens, 3, 6000, head_shared=True)
+    k2, _ = oracle.select(score[:, :1], lens, lens, 3, 6000)
+    np.testing.assert_array_equal(k1, k2)
+    k3, _ = oracle.select(score[:, ::-1].copy(), lens, lens, 3, 6000, head_shared=True)
+    k4, _ = oracle.select(score, lens, lens, 3, 6000, head_shared=True)
+    np.testing.assert_array_equal(k3, k4)
+
+
 # --------------------------------------------------------------------------
 # sparse attention and compaction
 # --------------------------------------------------------------------------
