@@ -71,7 +71,7 @@ typedef struct {
                             call: lets swa_decode_step size its LDS to the live cache instead of
                             cap.  A sequence that exceeds it is skipped and reported exactly like
                             a full cache (capacity status bit). */
-    int32_t flags;       /* 0, SWA_FUSE_COMPACTION, or SWA_FUSE_COMPACTION | SWA_UNORDERED */
+    int32_t flags;       /* 0 or a combination of the SWA_* flag bits below */
 } swa_params;
 
 /*
@@ -106,6 +106,17 @@ typedef struct {
  */
 #define SWA_UNORDERED 2
 #define SWA_MAX_UNORDERED_SLOTS 7168
+
+/*
+ * swa_params.flags bit, only together with SWA_FUSE_COMPACTION | SWA_UNORDERED: the local attention
+ * sum is reduced along the head dimension before the selection (the note in Algorithm 1's header):
+ * the globally dynamic tokens of sequence s are the top-k of sum_hd score[s, hd, i], and all heads
+ * of the sequence keep the same token set.  score stays per head (each head accumulates its own
+ * attention weights); the sum over the heads is taken in fp32, head 0 first.  The call enqueues two
+ * kernels (stream, publish; then reduce, select, finish) and needs the larger workspace that
+ * swa_workspace_bytes reports for these flags.
+ */
+#define SWA_HEAD_SHARED 4
 
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);

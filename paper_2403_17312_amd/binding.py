@@ -26,6 +26,7 @@ SWA_W_EVEN_SPLIT = -1
 SWA_FUSE_COMPACTION = 1
 SWA_MAX_FUSED_SLOTS = 9216
 SWA_UNORDERED = 2
+SWA_HEAD_SHARED = 4
 SWA_MAX_UNORDERED_SLOTS = 7168
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}

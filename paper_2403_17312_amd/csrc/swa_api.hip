@@ -28,6 +28,12 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes)
     return SWA_OK;
 }
 
+size_t shared_workspace_offset(const swa_params& p)
+{
+    const size_t head = kWsArriveOffset + sizeof(int32_t) * (size_t)p.b;
+    return (head + 255) & ~(size_t)255;
+}
+
 int decode_stash_rows(const swa_params& p)
 {
     // window + a margin for evictions a little behind it; bounded so LDS keeps several
@@ -71,7 +77,7 @@ __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)
 
 int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stream)
 {
-    const int64_t n = (int64_t)(swa_workspace_bytes(&p) / 4);
+    const int64_t n = (int64_t)(shared_workspace_offset(p) / 4);   // status word and arrival counters
     hipLaunchKernelGGL(swa_fill_zero_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, stream,
                        static_cast<int32_t*>(workspace), n);
     return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
@@ -88,8 +94,9 @@ static int validate(const swa_params* p)
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
     if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
-    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
+    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED | SWA_HEAD_SHARED)) return SWA_ERR_BAD_SHAPE;
     if ((p->flags & SWA_UNORDERED) && !(p->flags & SWA_FUSE_COMPACTION)) return SWA_ERR_BAD_SHAPE;
+    if ((p->flags & SWA_HEAD_SHARED) && !(p->flags & SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
     return SWA_OK;
 }
 
@@ -123,7 +130,9 @@ const char* swa_strerror(int code)
 size_t swa_workspace_bytes(const swa_params* params)
 {
     if (swa::validate(params) != SWA_OK) return 0;
-    const size_t bytes = swa::kWsArriveOffset + sizeof(int32_t) * (size_t)params->b;
+    size_t bytes = swa::shared_workspace_offset(*params);
+    if (params->flags & SWA_HEAD_SHARED)
+        bytes += sizeof(float) * ((size_t)params->b * params->h * params->cap * 2 + (size_t)params->b * params->h * params->d);
     return (bytes + 255) & ~(size_t)255;
 }
 

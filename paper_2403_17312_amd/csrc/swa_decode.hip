@@ -51,6 +51,13 @@ struct DecodeArgs {
     float scale;
     int32_t fuse_compaction;
     int32_t unordered;    // fused compaction fills holes instead of shifting rows (order by pos only)
+    // Head-shared selection runs as two launches: phase 1 streams the cache and publishes the new
+    // importance, the attention weights and the dense output of every pair; phase 2 sums the
+    // importance over the heads of the sequence, selects once, and finishes output and compaction.
+    int32_t phase;        // 0 = whole step in one launch
+    float* ws_p;          // [b,h,cap] attention weights of phase 1
+    float* ws_snew;       // [b,h,cap] new importance of phase 1 (read across heads in phase 2)
+    float* ws_abar;       // [b,h,d]   dense attention output of phase 1
     int32_t stash_rows;   // fused compaction: newest rows kept in LDS during the streaming pass
 };
 
@@ -161,6 +168,16 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         // first stashed slot (m = nothing stashed: only the streaming schedule fills the stash)
         const int stash_lo = (fc && fused) ? (m > a.stash_rows ? m - a.stash_rows : 0) : m;
 
+        float acc[EPV];           // fused pass: running sum of exp(z - Mg) * v
+#pragma unroll
+        for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
+        float mx = 0.f;           // global max of the logits (reference of the wave partials)
+        // (key << 32 | ~t): min = lowest score, then highest t; t is the slot, or the token
+        // position when slots are unordered.  The slot rides along as payload.
+        unsigned long long best = ~0ull;
+        int bslot = m;
+
+        if (a.phase != 2) {
         // ---- importance prefetch: the old values are needed only after the softmax ----
         float sold[SPF];
 #pragma unroll
@@ -192,9 +209,6 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 
         float Mg = -INFINITY;     // running max of this group's logits
         float Sg = 0.f;           // fused pass: running sum of exp(z - Mg)
-        float acc[EPV];           // fused pass: running sum of exp(z - Mg) * v
-#pragma unroll
-        for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
 
         if (fused) {
             // ---- one pass over key AND value rows, flash-style accumulators ---------
@@ -307,7 +321,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         __syncthreads();
 
         // ---- softmax over the m cached slots ------------------------------------------
-        float mx = s_redA[0];
+        mx = s_redA[0];
 #pragma unroll
         for (int v = 1; v < NW; ++v) mx = fmaxf(mx, s_redA[v]);
         float sum = 0.f;
@@ -324,10 +338,6 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         for (int v = 0; v < NW; ++v) sum += s_redB[v];
 
         // ---- importance accumulation; arg-min bookkeeping for the E == 1 case ------------
-        // (key << 32 | ~t): min = lowest score, then highest t; t is the slot, or the token
-        // position when slots are unordered.  The slot rides along as payload.
-        unsigned long long best = ~0ull;
-        int bslot = m;
 #pragma unroll
         for (int k = 0; k < SPF; ++k) {
             const int i = tid + k * NT;
@@ -340,6 +350,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     s_pos[i] = pold[k];
                 } else {
                     Sp[i] = sc;
+                }
+                if (a.phase == 1) {
+                    a.ws_snew[pair * (int64_t)cap + i] = sc;
+                    a.ws_p[pair * (int64_t)cap + i] = p;
                 }
                 const uint32_t key = order_key(sc);
                 s_key[i] = key;
@@ -365,6 +379,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             } else {
                 Sp[i] = sc;
             }
+            if (a.phase == 1) {
+                a.ws_snew[pair * (int64_t)cap + i] = sc;
+                a.ws_p[pair * (int64_t)cap + i] = p;
+            }
             const uint32_t key = order_key(sc);
             s_key[i] = key;
             if (bag ? (posi < wlo) : (i < ncand)) {
@@ -380,6 +398,54 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             __syncthreads();
             float* dbg = a.probs_dbg + pair * (int64_t)cap;
             for (int i = tid; i < cap; i += NT) dbg[i] = (i < m) ? s_p[i] : 0.f;
+        }
+
+        if (a.phase == 1) {
+            // publish the dense output; phase 2 subtracts the evicted rows from it
+            if (fused) {
+                for (int e = tid; e < D; e += NT) {
+                    float St = 0.f, At = 0.f;
+#pragma unroll
+                    for (int v = 0; v < NW; ++v) {
+                        const float r = fast_exp2((s_redA[v] - mx) * kLog2e);
+                        St = __builtin_fmaf(s_wS[v], r, St);
+                        At = __builtin_fmaf(s_acc[v * D + e], r, At);
+                    }
+                    a.ws_abar[pair * D + e] = At / St;
+                }
+            }
+            return;
+        }
+        } else {
+            // ---- phase 2 of the head-shared step: reload what phase 1 published --------------
+            if (tid == 0) s_ecnt = 0;
+            const float* Pw = a.ws_p + pair * (int64_t)cap;
+            const float* Sn = a.ws_snew + pair * (int64_t)cap;
+            const float* Sh = a.ws_snew + (int64_t)s * a.h * cap;     // head 0 of this sequence
+            for (int i = tid; i < m; i += NT) {
+                s_p[i] = Pw[i];
+                s_sc[i] = Sn[i];
+                const int posi = (i < len) ? Pp[i] : (n - 1);
+                s_pos[i] = posi;
+                float tot = 0.f;                                       // fixed order: head 0, 1, ...
+                for (int hh = 0; hh < a.h; ++hh) tot += Sh[(int64_t)hh * cap + i];
+                const uint32_t key = order_key(tot);
+                s_key[i] = key;
+                if (posi < wlo) {
+                    const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)posi);
+                    if (c < best) {
+                        best = c;
+                        bslot = i;
+                    }
+                }
+            }
+            // the dense output stands in for the wave partials of the streaming pass
+            for (int e = tid; e < D; e += NT) s_acc[e] = fused ? a.ws_abar[pair * D + e] : 0.f;
+            if (tid < 16) {
+                s_redA[tid] = (tid == 0) ? 0.f : -INFINITY;
+                s_wS[tid] = (tid == 0) ? 1.f : 0.f;
+            }
+            mx = 0.f;
         }
 
         // ---- selection ---------------------------------------------------------------------
@@ -849,6 +915,16 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.scale = scale;
     a.fuse_compaction = (p.flags & SWA_FUSE_COMPACTION) ? 1 : 0;
     a.unordered = (a.fuse_compaction && (p.flags & SWA_UNORDERED)) ? 1 : 0;
+    const bool shared = a.unordered && (p.flags & SWA_HEAD_SHARED);
+    a.phase = 0;
+    a.ws_p = a.ws_snew = a.ws_abar = nullptr;
+    if (shared) {
+        char* base = static_cast<char*>(workspace) + shared_workspace_offset(p);
+        const size_t slab = (size_t)p.b * p.h * p.cap * sizeof(float);
+        a.ws_p = reinterpret_cast<float*>(base);
+        a.ws_snew = reinterpret_cast<float*>(base + slab);
+        a.ws_abar = reinterpret_cast<float*>(base + 2 * slab);
+    }
     a.stash_rows = (a.fuse_compaction && !a.unordered) ? decode_stash_rows(p) : 0;
 
     const int64_t pairs = (int64_t)p.b * p.h;
@@ -857,16 +933,23 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
                              (size_t)a.stash_rows * rowb * 2;
     const int nt = decode_block_threads(pairs, bound);
 
-    if (p.dtype == SWA_F32) {
-        return p.d == 64 ? launch_decode_t<F32, 64>(a, pairs, lds_bytes, nt, stream)
-                         : launch_decode_t<F32, 128>(a, pairs, lds_bytes, nt, stream);
-    } else if (p.dtype == SWA_F16) {
-        return p.d == 64 ? launch_decode_t<F16, 64>(a, pairs, lds_bytes, nt, stream)
-                         : launch_decode_t<F16, 128>(a, pairs, lds_bytes, nt, stream);
-    } else {
-        return p.d == 64 ? launch_decode_t<BF16, 64>(a, pairs, lds_bytes, nt, stream)
-                         : launch_decode_t<BF16, 128>(a, pairs, lds_bytes, nt, stream);
-    }
+    auto launch = [&](const DecodeArgs& args) -> int {
+        if (p.dtype == SWA_F32) {
+            return p.d == 64 ? launch_decode_t<F32, 64>(args, pairs, lds_bytes, nt, stream)
+                             : launch_decode_t<F32, 128>(args, pairs, lds_bytes, nt, stream);
+        } else if (p.dtype == SWA_F16) {
+            return p.d == 64 ? launch_decode_t<F16, 64>(args, pairs, lds_bytes, nt, stream)
+                             : launch_decode_t<F16, 128>(args, pairs, lds_bytes, nt, stream);
+        }
+        return p.d == 64 ? launch_decode_t<BF16, 64>(args, pairs, lds_bytes, nt, stream)
+                         : launch_decode_t<BF16, 128>(args, pairs, lds_bytes, nt, stream);
+    };
+    if (!shared) return launch(a);
+    a.phase = 1;
+    int rc = launch(a);
+    if (rc != SWA_OK) return rc;
+    a.phase = 2;
+    return launch(a);
 }
 
 }  // namespace swa

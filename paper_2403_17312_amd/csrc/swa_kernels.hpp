@@ -16,6 +16,10 @@ int ensure_dynamic_lds(const void* kernel, size_t bytes);
 // this bound on the cached length.
 int decode_block_threads(int64_t pairs, int len_bound);
 
+// Byte offset, inside the caller's workspace, of the slabs the head-shared step passes from its
+// first launch to its second (present only when SWA_HEAD_SHARED is set).
+size_t shared_workspace_offset(const swa_params& p);
+
 // Rows of K and V the fused-compaction decode parks in LDS (0 = none).
 int decode_stash_rows(const swa_params& p);
 

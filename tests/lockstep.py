@@ -81,7 +81,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
                  prompt: Optional[dict] = None, verbose: bool = False,
                  use_len_bound: bool = False, fused: bool = False, unordered: bool = False,
-                 sparsity_of_step=None) -> Report:
+                 sparsity_of_step=None, head_shared: bool = False) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
@@ -93,6 +93,13 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         # swa_decode_step with SWA_FUSE_COMPACTION: one kernel does the step and the compaction
         assert compact_every == 1
         st.params.flags = B.SWA_FUSE_COMPACTION | (B.SWA_UNORDERED if unordered else 0)
+        if head_shared:
+            # one token set per sequence from the head-summed importance: every head of a sampled
+            # sequence is needed, and the workspace carries the slabs between the two launches
+            assert unordered and len(heads) == wl.h
+            st.params.flags |= B.SWA_HEAD_SHARED
+            st.workspace = torch.zeros((B.swa_workspace_bytes(st.params),), dtype=torch.uint8, device=device)
+            B.swa_workspace_init(st.params, st.workspace)
     else:
         assert not unordered
     # Unordered compaction keeps the cache as a set: every GPU tensor is brought into token order
@@ -146,7 +153,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         # ---- oracle step from the adopted state ---------------------------------
         q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
         kept_o, cnt_o, out_o, p_o = O.decode_step(q_o, kn_o, vn_o, K_o, V_o, score_o, pos_o, len_o,
-                                                  n_o, wl.w, sp_t, wl.scale)
+                                                  n_o, wl.w, sp_t, wl.scale, head_shared=head_shared)
         kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
         if fused:
             # the cache is already compacted: the new lengths are in cache_len (swapped in),
@@ -209,7 +216,15 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                 rep.max_score_rel = max(rep.max_score_rel,
                                         float(np.max(se / (np.abs(score_o[i, :, :m]) + 1e-30))))
             # (ii) index sets: oracle selection on the GPU's own fp32 scores, bit-exact
-            kept_ref, cnt_ref = O.select(score_g, len_o, n_o, wl.w, sp_t)
+            if head_shared:
+                # the kernel sums the heads in fp32, head 0 first: take the decision in that precision
+                tot32 = np.zeros((score_g.shape[0], score_g.shape[2]), dtype=np.float32)
+                for hd in range(len(heads)):
+                    tot32 = (tot32 + score_g[:, hd].astype(np.float32)).astype(np.float32)
+                k1, cnt_ref = O.select(tot32[:, None, :].astype(np.float64), len_o, n_o, wl.w, sp_t)
+                kept_ref = np.repeat(k1, len(heads), axis=1)
+            else:
+                kept_ref, cnt_ref = O.select(score_g, len_o, n_o, wl.w, sp_t)
             assert np.array_equal(cnt_ref, cnt_g)
             for i, c in enumerate(cnt_g):
                 assert np.array_equal(kept_g[i, :, :c], kept_ref[i, :, :c]), \
@@ -221,10 +236,11 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                     if diff:
                         m = len_o[i]
                         nl = O.budget(int(n_o[i]), int(m), wl.w, sp_t)[1]
-                        cand = np.sort(score_o[i, hd, :m - nl])[::-1]
+                        sel_o = score_o[i].sum(axis=0) if head_shared else score_o[i, hd]
+                        cand = np.sort(sel_o[:m - nl])[::-1]
                         cutoff = cand[c - nl - 1]
                         for j in diff:
-                            assert abs(score_o[i, hd, j] - cutoff) <= 2e-5 * abs(cutoff), \
+                            assert abs(sel_o[j] - cutoff) <= 2e-5 * abs(cutoff), \
                                 f"step {t}: flipped token {j} is not a near tie"
                         rep.near_tie_flips += len(diff) // 2
             # (iii) output on the GPU's kept set

@@ -45,6 +45,7 @@ def test_params_struct_matches_header(B):
     assert int(re.search(r"#define SWA_MAX_FUSED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_FUSED_SLOTS
     assert int(re.search(r"#define SWA_FUSE_COMPACTION (\d+)", text).group(1)) == B.SWA_FUSE_COMPACTION
     assert int(re.search(r"#define SWA_UNORDERED (\d+)", text).group(1)) == B.SWA_UNORDERED
+    assert int(re.search(r"#define SWA_HEAD_SHARED (\d+)", text).group(1)) == B.SWA_HEAD_SHARED
     assert int(re.search(r"#define SWA_MAX_UNORDERED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_UNORDERED_SLOTS
 
 
@@ -75,6 +76,8 @@ def test_workspace_bytes(B):
     n = B.swa_workspace_bytes(p)
     assert n >= 64 + 4 * 16 and n % 256 == 0
     assert B.swa_workspace_bytes(B.make_params(16, 32, 96, 545, 16, 8000, B.SWA_F16)) == 0
+    ps = B.make_params(16, 32, 128, 576, 16, 8000, B.SWA_F16, flags=7)
+    assert B.swa_workspace_bytes(ps) >= n + 4 * (2 * 16 * 32 * 576 + 16 * 32 * 128)
 
 
 @pytest.mark.parametrize("kw,code", [
@@ -86,7 +89,9 @@ def test_workspace_bytes(B):
     (dict(cap=16385), "SWA_ERR_CAPACITY"),
     (dict(len_bound=-1), "SWA_ERR_BAD_SHAPE"),
     (dict(flags=2), "SWA_ERR_BAD_SHAPE"),          # SWA_UNORDERED needs SWA_FUSE_COMPACTION
-    (dict(flags=4), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=4), "SWA_ERR_BAD_SHAPE"),          # SWA_HEAD_SHARED needs the other two
+    (dict(flags=5), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=8), "SWA_ERR_BAD_SHAPE"),
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
     (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),

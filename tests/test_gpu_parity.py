@@ -150,6 +150,44 @@ def test_even_split_of_algorithm_1_in_every_step_mode(env):
     assert rep.steps == 32
 
 
+def test_head_shared_selection_matches_the_oracle(env):
+    # SWA_HEAD_SHARED: the local attention sum is reduced over the heads, one token set per sequence
+    O, B, W, LS = env
+    _say("head-shared selection")
+    rep = LS.run_lockstep(W.CONFIGS["c1_tiny"], fused=True, unordered=True, head_shared=True)
+    assert rep.steps == 16 and rep.evictions > 0
+    for dtype, d, w in [("f16", 128, 7), ("bf16", 64, 0), ("f32", 128, B.SWA_W_EVEN_SPLIT)]:
+        wl = W.Workload(f"t_sh_{dtype}", 35, b=3, h=5, d=d, dtype=dtype, prompt_lo=2, prompt_hi=333,
+                        steps=12, w=w, sparsity_bp=7000, hh_frac=0.02, prefill_R=5)
+        rep = LS.run_lockstep(wl, fused=True, unordered=True, head_shared=True)
+        assert rep.evictions > 0
+    # a budget that tightens later (many evictions at once on a cache out of token order)
+    wl = W.Workload("t_sh_sched", 36, b=2, h=4, d=128, dtype="f16", prompt_lo=60, prompt_hi=90,
+                    steps=20, w=4, sparsity_bp=3000, hh_frac=0.02)
+    LS.run_lockstep(wl, fused=True, unordered=True, head_shared=True,
+                    sparsity_of_step=lambda t: 3000 if t < 10 else (8500 if t < 12 else 6000))
+    # config 2 at full size, every pair
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], fused=True, unordered=True, head_shared=True,
+                          use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+    # every head of a sequence ends with the same tokens
+    wl = W.CONFIGS["c2_opt6p7b"]
+    prompt = W.make_prompt(wl, "cuda")
+    st = LS.new_state(wl, prompt, debug_probs=False)
+    st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED
+    st.workspace = torch.zeros((B.swa_workspace_bytes(st.params),), dtype=torch.uint8, device="cuda")
+    B.swa_workspace_init(st.params, st.workspace)
+    st.score.zero_()
+    for t in range(6):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        st.decode_compact_step(q, kn, vn)
+    L = int(st.cache_len[0])
+    srt = st.pos[:, :, :L].sort(dim=-1).values
+    assert torch.equal(srt, srt[:, :1].expand_as(srt))
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
