@@ -56,9 +56,10 @@ class Replica:
     def __init__(self, B, W, wl, prompt, torch, len_bounds, fused):
         self.fused = bool(fused)
         flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
-                 "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED}[fused]
+                 "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED,
+                 "shared": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED}[fused]
         self.fused = flags != 0
-        params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+        params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, flags=flags)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
         st.K.copy_(prompt["K"])
         st.V.copy_(prompt["V"])
@@ -292,9 +293,11 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default="c2_opt6p7b")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
-    ap.add_argument("--step-mode", choices=["unordered", "fused", "split"], default="unordered",
+    ap.add_argument("--step-mode", choices=["unordered", "fused", "split", "shared"], default="unordered",
                     help="fused: one kernel per step, cache kept in token order; unordered: one kernel per "
-                         "step, compaction fills holes (SWA_UNORDERED); split: swa_decode_step + swa_compact_kv")
+                         "step, compaction fills holes (SWA_UNORDERED); shared: unordered with one token set per "
+                         "sequence from the head-summed importance (SWA_HEAD_SHARED, two launches); "
+                         "split: swa_decode_step + swa_compact_kv")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -326,7 +329,7 @@ def main():
     # rocprofv3's per-kernel average (profiles/).  Split mode: per-launch event brackets.
     dec_ms = res["ms_per_step"] if fused else res["decode_kernel_ms_avg"]
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
-    traffic = load_traffic(wl.name) if fused else None
+    traffic = load_traffic(wl.name) if args.step_mode == "unordered" else None
     line = {
         "metric": "SWA decode-step KV tokens/s",
         "value": res["kv_tokens_per_s"],
@@ -342,6 +345,8 @@ def main():
                                          "hole-filling compaction, kept_idx not requested)",
                             "fused": "swa_decode_step with SWA_FUSE_COMPACTION (one kernel, token-ordered "
                                      "compaction, kept_idx not requested)",
+                            "shared": "swa_decode_step with SWA_HEAD_SHARED (two launches around the "
+                                      "head-summed importance, hole-filling compaction)",
                             "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]},
         "roofline": {
             "bound": "hbm", "kernel": "swa_decode_kernel",
