@@ -43,6 +43,19 @@
  *     attention sum reduced over the heads, as Algorithm 1's header notes --
  *     and ties go to the lowest slot;
  *   - the kept list is in ascending slot order and compaction preserves it.
+ *
+ * KV compression (Section V-B): the three quantisation routines at the end of
+ * this file are the one place where single precision is used on purpose.  A
+ * code is an integer decided by floating-point arithmetic, so the decision is
+ * taken in the precision of the device library (IEEE fp32, one rounding per
+ * operation, no contraction); de-quantisation back to the values the attention
+ * reads is exact in fp64.  Readings: 8-bit unsigned codes; one (scale,
+ * zero-point) pair per channel of every (sequence, head) pair, taken over the
+ * cached tokens when the cache is quantised; the printed zero-point formula is
+ * garbled, the zero point is nearest-integer(-min / scale) so that min maps to
+ * code 0; "round" is nearest with ties to even; codes saturate at 0 and 255
+ * (tokens appended later reuse the parameters); a channel whose range is below
+ * 2^-7 takes that range, so the scale is never zero.
  */
 #include <math.h>
 #include <stdint.h>
@@ -254,7 +267,7 @@ int swa_oracle_select_shared(int32_t b, int32_t h, int32_t cap, int32_t w, int32
                              const double *score, const int32_t *cache_len, const int32_t *seq_len,
                              int32_t *kept_idx, int32_t *kept_cnt)
 {
-    double *summed = (double *)malloc(sizeof(double) * (size_t)b * cap);
+    double *summed = (double *)calloc((size_t)b * cap, sizeof(double));
     int32_t *one = (int32_t *)malloc(sizeof(int32_t) * (size_t)b * cap);
     if (!summed || !one) {
         free(summed);
@@ -451,4 +464,80 @@ int swa_oracle_prefill_scores(int32_t b, int32_t h, int32_t d, int32_t cap, int3
         free(aw);
     }
     return failed ? SWA_ORACLE_ERR_ALLOC : SWA_ORACLE_OK;
+}
+
+
+/* ------------------------------------------------------------------------ */
+/* KV compression (Section V-B): x_q = round(x / lambda + z),               */
+/* x = lambda * (x_q - z), lambda = (max - min) / (2^8 - 1).                */
+/* X [b,h,rows,d] holds values exactly representable in fp32; count[s] rows */
+/* of every pair of sequence s are valid.  lambda, zero: [b,h,d] fp32.      */
+/* ------------------------------------------------------------------------ */
+#define SWA_ORACLE_MIN_RANGE 0.0078125f /* 2^-7 */
+
+void swa_oracle_kv_qparams(int32_t b, int32_t h, int32_t d, int32_t rows, const double *X,
+                           const int32_t *count, float *lambda, float *zero)
+{
+    int64_t pairs = (int64_t)b * h;
+#pragma omp parallel for schedule(static)
+    for (int64_t pr = 0; pr < pairs; ++pr) {
+        int32_t cnt = count[pr / h];
+        const double *Xp = X + pr * (int64_t)rows * d;
+        for (int32_t c = 0; c < d; ++c) {
+            float lo = 0.0f, hi = 0.0f;
+            for (int32_t i = 0; i < cnt; ++i) {
+                float x = (float)Xp[(int64_t)i * d + c];
+                if (i == 0 || x < lo) lo = x;
+                if (i == 0 || x > hi) hi = x;
+            }
+            float range = hi - lo;
+            if (range < SWA_ORACLE_MIN_RANGE) range = SWA_ORACLE_MIN_RANGE;
+            float lam = range / 255.0f;
+            float t = -lo / lam;
+            lambda[pr * d + c] = lam;
+            zero[pr * d + c] = rintf(t);
+        }
+    }
+}
+
+static uint8_t quantise_one(float x, float lam, float z)
+{
+    float t = x / lam;
+    t = t + z;
+    t = rintf(t);
+    if (t < 0.0f) t = 0.0f;
+    if (t > 255.0f) t = 255.0f;
+    return (uint8_t)t;
+}
+
+void swa_oracle_kv_quantize(int32_t b, int32_t h, int32_t d, int32_t rows, const double *X,
+                            const int32_t *count, const float *lambda, const float *zero,
+                            uint8_t *codes)
+{
+    int64_t pairs = (int64_t)b * h;
+#pragma omp parallel for schedule(static)
+    for (int64_t pr = 0; pr < pairs; ++pr) {
+        int32_t cnt = count[pr / h];
+        for (int32_t i = 0; i < cnt; ++i)
+            for (int32_t c = 0; c < d; ++c) {
+                int64_t at = (pr * rows + i) * (int64_t)d + c;
+                codes[at] = quantise_one((float)X[at], lambda[pr * d + c], zero[pr * d + c]);
+            }
+    }
+}
+
+void swa_oracle_kv_dequantize(int32_t b, int32_t h, int32_t d, int32_t rows, const uint8_t *codes,
+                              const int32_t *count, const float *lambda, const float *zero,
+                              double *X)
+{
+    int64_t pairs = (int64_t)b * h;
+#pragma omp parallel for schedule(static)
+    for (int64_t pr = 0; pr < pairs; ++pr) {
+        int32_t cnt = count[pr / h];
+        for (int32_t i = 0; i < cnt; ++i)
+            for (int32_t c = 0; c < d; ++c) {
+                int64_t at = (pr * rows + i) * (int64_t)d + c;
+                X[at] = (double)lambda[pr * d + c] * ((double)codes[at] - (double)zero[pr * d + c]);
+            }
+    }
 }

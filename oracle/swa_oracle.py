@@ -173,3 +173,50 @@ def prefill_scores(q_tail, K, cache_len, scale: float):
                                          _pd(q_tail), _pd(K), _pi(_i32(cache_len)), _pd(score))
     _check(rc, "prefill_scores")
     return score
+
+
+def _pf(a):
+    assert a.dtype == np.float32 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_float))
+
+
+def _pu8(a):
+    assert a.dtype == np.uint8 and a.flags["C_CONTIGUOUS"]
+    return a.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8))
+
+
+def _rows_dims(X):
+    b, h, rows, d = X.shape
+    return ctypes.c_int32(b), ctypes.c_int32(h), ctypes.c_int32(d), ctypes.c_int32(rows)
+
+
+def kv_qparams(X, count):
+    """Channel-wise scale and zero point, fp32 [b,h,d] each, over rows 0..count[s]-1 of X [b,h,rows,d]."""
+    X = _f64(X)
+    b, h, d, rows = _rows_dims(X)
+    lam = np.zeros((X.shape[0], X.shape[1], X.shape[3]), dtype=np.float32)
+    zero = np.zeros_like(lam)
+    lib().swa_oracle_kv_qparams(b, h, d, rows, _pd(X), _pi(_i32(count)), _pf(lam), _pf(zero))
+    return lam, zero
+
+
+def kv_quantize(X, count, lam, zero):
+    """uint8 codes [b,h,rows,d] of the valid rows of X (the rest 0)."""
+    X = _f64(X)
+    b, h, d, rows = _rows_dims(X)
+    codes = np.zeros(X.shape, dtype=np.uint8)
+    lib().swa_oracle_kv_quantize(b, h, d, rows, _pd(X), _pi(_i32(count)),
+                                 _pf(np.ascontiguousarray(lam, dtype=np.float32)),
+                                 _pf(np.ascontiguousarray(zero, dtype=np.float32)), _pu8(codes))
+    return codes
+
+
+def kv_dequantize(codes, count, lam, zero):
+    """float64 [b,h,rows,d]: scale * (code - zero) on the valid rows (the rest 0)."""
+    codes = np.ascontiguousarray(codes, dtype=np.uint8)
+    b, h, d, rows = _rows_dims(codes)
+    X = np.zeros(codes.shape, dtype=np.float64)
+    lib().swa_oracle_kv_dequantize(b, h, d, rows, _pu8(codes), _pi(_i32(count)),
+                                   _pf(np.ascontiguousarray(lam, dtype=np.float32)),
+                                   _pf(np.ascontiguousarray(zero, dtype=np.float32)), _pd(X))
+    return X
