@@ -118,6 +118,14 @@ typedef struct {
  */
 #define SWA_HEAD_SHARED 4
 
+/*
+ * swa_params.flags bit: k_cache and v_cache hold 8-bit codes (Section V-B, KV compression): rows
+ * of d bytes, [b,h,cap,d] uint8, produced by swa_quantize_kv.  dtype must be SWA_F16 (the format
+ * the paper de-quantises to) and describes q, k_new, v_new and out.  Set for
+ * swa_decode_step_q8 and for swa_compact_kv on such a cache; swa_decode_step refuses it.
+ */
+#define SWA_KV_INT8 8
+
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);
 
@@ -197,6 +205,40 @@ int swa_decode_step(const swa_params *params, const void *q, const void *k_new, 
 int swa_compact_kv(const swa_params *params, void *k_cache, void *v_cache, float *score,
                    int32_t *pos, const int32_t *kept_idx, const int32_t *kept_cnt,
                    int32_t *cache_len, void *workspace, void *stream);
+
+/*
+ * KV compression, Section V-B: x_q = round(x / lambda + z), x = lambda (x_q - z),
+ * lambda = (max - min) / (2^8 - 1), channel-wise.  For every pair and every channel c < d the
+ * extrema run over the cached tokens 0..cache_len[s]-1; z = nint(-min / lambda) (the code that min
+ * maps to 0 with; the paper's printed zero point is garbled); "round" is to nearest, ties to
+ * even; codes saturate at 0 and 255; a channel whose range is below 2^-7 (or an empty cache)
+ * takes that range.  All of it in fp32, one rounding per operation.
+ *   k_cache, v_cache [b,h,cap,d] fp16 (in); cache_len [b] (in);
+ *   k_codes, v_codes [b,h,cap,d] uint8 (out; slots >= cache_len untouched);
+ *   qparams [4, b,h,d] float32 (out): lambda_K, z_K, lambda_V, z_V.
+ * params->dtype must be SWA_F16; SWA_KV_INT8 in flags is accepted and ignored.
+ */
+int swa_quantize_kv(const swa_params *params, const void *k_cache, const void *v_cache,
+                    const int32_t *cache_len, void *k_codes, void *v_codes, float *qparams,
+                    void *stream);
+
+/*
+ * swa_decode_step over a compressed cache (Section V-B: KV tensors are integers in memory and
+ * are de-quantised for the computation).  Same steps, arguments and flag variants as
+ * swa_decode_step, except
+ *   - params->flags must contain SWA_KV_INT8, dtype must be SWA_F16;
+ *   - k_codes, v_codes [b,h,cap,d] uint8 (in/out) take the place of k_cache, v_cache;
+ *   - qparams [4, b,h,d] float32 (in) as written by swa_quantize_kv;
+ *   - the new token's k_new, v_new (fp16) are quantised with the pair's parameters on arrival
+ *     (saturating), and the step attends over the de-quantised codes of all m slots, the new
+ *     one included: every value the attention reads is lambda_c (code - z_c), exactly.
+ * Scores are accumulated in fp32 as q_c lambda_c times the code; out is rounded once to fp16.
+ */
+int swa_decode_step_q8(const swa_params *params, const void *q, const void *k_new,
+                       const void *v_new, void *k_codes, void *v_codes, const float *qparams,
+                       float *score, int32_t *pos, int32_t *cache_len, const int32_t *seq_len,
+                       int32_t *kept_idx, int32_t *kept_cnt, void *out, float *probs_dbg,
+                       void *workspace, void *stream);
 
 #ifdef __cplusplus
 }

@@ -28,10 +28,12 @@ SWA_MAX_FUSED_SLOTS = 9216
 SWA_UNORDERED = 2
 SWA_HEAD_SHARED = 4
 SWA_MAX_UNORDERED_SLOTS = 7168
+SWA_KV_INT8 = 8
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
-           "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv"]
+           "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
+           "swa_decode_step_q8"]
 
 
 class SwaParams(ctypes.Structure):
@@ -77,6 +79,10 @@ def lib():
         L.swa_decode_step.argtypes = [pp] + [vp] * 15
         L.swa_compact_kv.restype = ctypes.c_int
         L.swa_compact_kv.argtypes = [pp] + [vp] * 9
+        L.swa_quantize_kv.restype = ctypes.c_int
+        L.swa_quantize_kv.argtypes = [pp] + [vp] * 7
+        L.swa_decode_step_q8.restype = ctypes.c_int
+        L.swa_decode_step_q8.argtypes = [pp] + [vp] * 16
         _lib = L
     return _lib
 
@@ -149,6 +155,23 @@ def swa_decode_step(params: SwaParams, q, k_new, v_new, k_cache, v_cache, score,
            "swa_decode_step")
 
 
+def swa_quantize_kv(params: SwaParams, k_cache, v_cache, cache_len, k_codes, v_codes, qparams,
+                    stream=None) -> None:
+    _check(lib().swa_quantize_kv(ctypes.byref(params), _ptr(k_cache), _ptr(v_cache), _ptr(cache_len),
+                                 _ptr(k_codes), _ptr(v_codes), _ptr(qparams), _stream(stream)),
+           "swa_quantize_kv")
+
+
+def swa_decode_step_q8(params: SwaParams, q, k_new, v_new, k_codes, v_codes, qparams, score, pos,
+                       cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace,
+                       stream=None) -> None:
+    _check(lib().swa_decode_step_q8(ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                    _ptr(k_codes), _ptr(v_codes), _ptr(qparams), _ptr(score),
+                                    _ptr(pos), _ptr(cache_len), _ptr(seq_len), _ptr(kept_idx),
+                                    _ptr(kept_cnt), _ptr(out), _ptr(probs_dbg), _ptr(workspace),
+                                    _stream(stream)), "swa_decode_step_q8")
+
+
 def swa_compact_kv(params: SwaParams, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,
                    workspace, stream=None) -> None:
     _check(lib().swa_compact_kv(ctypes.byref(params), _ptr(k_cache), _ptr(v_cache), _ptr(score),
@@ -177,18 +200,36 @@ class DecodeState:
         self.workspace = torch.zeros((swa_workspace_bytes(params),), dtype=torch.uint8,
                                      device=device)
         swa_workspace_init(params, self.workspace)
+        self.qparams = None     # [4,b,h,d] float32 once the cache is compressed
+
+    def quantize(self, stream=None) -> None:
+        """Replaces the fp16 K, V tensors by their 8-bit codes (swa_quantize_kv) and switches the
+        params to SWA_KV_INT8."""
+        codesK, codesV = torch.zeros_like(self.K, dtype=torch.uint8), torch.zeros_like(self.V, dtype=torch.uint8)
+        p = self.params
+        self.qparams = torch.zeros((4, p.b, p.h, p.d), dtype=torch.float32, device=self.K.device)
+        swa_quantize_kv(p, self.K, self.V, self.cache_len, codesK, codesV, self.qparams, stream)
+        self.K, self.V = codesK, codesV
+        p.flags |= SWA_KV_INT8
+
+    def _decode(self, params, q, k_new, v_new, cache_len, kept_idx, kept_cnt, stream) -> None:
+        if self.qparams is not None:
+            swa_decode_step_q8(params, q, k_new, v_new, self.K, self.V, self.qparams, self.score,
+                               self.pos, cache_len, self.seq_len, kept_idx, kept_cnt, self.out,
+                               self.probs, self.workspace, stream)
+        else:
+            swa_decode_step(params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
+                            cache_len, self.seq_len, kept_idx, kept_cnt, self.out, self.probs,
+                            self.workspace, stream)
 
     def decode_step(self, q, k_new, v_new, stream=None) -> None:
-        swa_decode_step(self.params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
-                        self.cache_len, self.seq_len, self.kept_idx, self.kept_cnt, self.out,
-                        self.probs, self.workspace, stream)
+        self._decode(self.params, q, k_new, v_new, self.cache_len, self.kept_idx, self.kept_cnt, stream)
 
     def decode_compact_step(self, q, k_new, v_new, stream=None, want_idx: bool = True) -> None:
         """Fused call (params.flags must carry SWA_FUSE_COMPACTION): the new lengths come back in
         kept_cnt, so the two length tensors are swapped afterwards."""
-        swa_decode_step(self.params, q, k_new, v_new, self.K, self.V, self.score, self.pos,
-                        self.cache_len, self.seq_len, self.kept_idx if want_idx else None,
-                        self.kept_cnt, self.out, self.probs, self.workspace, stream)
+        self._decode(self.params, q, k_new, v_new, self.cache_len,
+                     self.kept_idx if want_idx else None, self.kept_cnt, stream)
         self.cache_len, self.kept_cnt = self.kept_cnt, self.cache_len
 
     def compact(self, stream=None) -> None:

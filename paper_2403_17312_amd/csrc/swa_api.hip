@@ -48,7 +48,7 @@ int decode_stash_rows(const swa_params& p)
     const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
     if (rows > bound) rows = ((bound + 15) / 16) * 16;
     // long caches (first step after a prompt) take the gather schedule, which has no use for it
-    const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
+    const int rowb = cache_row_bytes(p);
     if ((size_t)((bound + 63) & ~63) * 16 + (size_t)rows * rowb * 2 > 96 * 1024) rows = 0;
     return rows;
 }
@@ -94,7 +94,8 @@ static int validate(const swa_params* p)
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
     if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
-    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED | SWA_HEAD_SHARED)) return SWA_ERR_BAD_SHAPE;
+    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED | SWA_HEAD_SHARED | SWA_KV_INT8)) return SWA_ERR_BAD_SHAPE;
+    if ((p->flags & SWA_KV_INT8) && p->dtype != SWA_F16) return SWA_ERR_UNSUPPORTED_DTYPE;
     if ((p->flags & SWA_UNORDERED) && !(p->flags & SWA_FUSE_COMPACTION)) return SWA_ERR_BAD_SHAPE;
     if ((p->flags & SWA_HEAD_SHARED) && !(p->flags & SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
     return SWA_OK;
@@ -187,13 +188,11 @@ int swa_prefill_scores(const swa_params* params, const void* q_tail, int32_t R, 
                                static_cast<hipStream_t>(stream));
 }
 
-int swa_decode_step(const swa_params* params, const void* q, const void* k_new, const void* v_new,
-                    void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
-                    const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
-                    float* probs_dbg, void* workspace, void* stream)
+static int decode_common(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, const float* qparams, float* score, int32_t* pos,
+                         int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt,
+                         void* out, float* probs_dbg, void* workspace, void* stream)
 {
-    int rc = swa::validate(params);
-    if (rc != SWA_OK) return rc;
     const bool fuse = (params->flags & SWA_FUSE_COMPACTION) != 0;
     if (!q || !k_new || !v_new || !k_cache || !v_cache || !score || !pos || !cache_len || !seq_len ||
         (!kept_idx && !fuse) || !kept_cnt || !out || !workspace)
@@ -207,8 +206,47 @@ int swa_decode_step(const swa_params* params, const void* q, const void* k_new, 
         !swa::aligned16(v_cache) || !swa::aligned16(out))
         return SWA_ERR_ALIGNMENT;
     return swa::launch_decode(*params, swa::effective_scale(params), q, k_new, v_new, k_cache, v_cache, score,
-                              pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace,
+                              pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, qparams,
                               static_cast<hipStream_t>(stream));
+}
+
+int swa_decode_step(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                    void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
+                    const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
+                    float* probs_dbg, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;   // codes need their parameters
+    return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
+                         kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+int swa_decode_step_q8(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                       void* k_codes, void* v_codes, const float* qparams, float* score, int32_t* pos,
+                       int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt,
+                       void* out, float* probs_dbg, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!(params->flags & SWA_KV_INT8)) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (!qparams) return SWA_ERR_NULL;
+    return decode_common(params, q, k_new, v_new, k_codes, v_codes, qparams, score, pos, cache_len, seq_len,
+                         kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+int swa_quantize_kv(const swa_params* params, const void* k_cache, const void* v_cache,
+                    const int32_t* cache_len, void* k_codes, void* v_codes, float* qparams, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (params->dtype != SWA_F16) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (!k_cache || !v_cache || !cache_len || !k_codes || !v_codes || !qparams) return SWA_ERR_NULL;
+    if (!swa::aligned16(k_cache) || !swa::aligned16(v_cache) || !swa::aligned16(k_codes) ||
+        !swa::aligned16(v_codes))
+        return SWA_ERR_ALIGNMENT;
+    return swa::launch_quantize(*params, k_cache, v_cache, cache_len, k_codes, v_codes, qparams,
+                                static_cast<hipStream_t>(stream));
 }
 
 int swa_compact_kv(const swa_params* params, void* k_cache, void* v_cache, float* score, int32_t* pos,

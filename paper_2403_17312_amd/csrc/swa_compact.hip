@@ -112,9 +112,10 @@ int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* sco
     a.h = p.h;
     a.cap = p.cap;
     const int64_t pairs = (int64_t)p.b * p.h;
-    const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
+    const int rowb = cache_row_bytes(p);
     constexpr int NT = 256;
     switch (rowb) {
+        case 64: hipLaunchKernelGGL((swa_compact_kernel<64, NT>), dim3((unsigned)pairs), dim3(NT), 0, stream, a); break;
         case 128: hipLaunchKernelGGL((swa_compact_kernel<128, NT>), dim3((unsigned)pairs), dim3(NT), 0, stream, a); break;
         case 256: hipLaunchKernelGGL((swa_compact_kernel<256, NT>), dim3((unsigned)pairs), dim3(NT), 0, stream, a); break;
         case 512: hipLaunchKernelGGL((swa_compact_kernel<512, NT>), dim3((unsigned)pairs), dim3(NT), 0, stream, a); break;

@@ -59,6 +59,10 @@ struct DecodeArgs {
     float* ws_snew;       // [b,h,cap] new importance of phase 1 (read across heads in phase 2)
     float* ws_abar;       // [b,h,d]   dense attention output of phase 1
     int32_t stash_rows;   // fused compaction: newest rows kept in LDS during the streaming pass
+    // Compressed cache (Section V-B): per (pair, channel) scale and zero point of keys and values,
+    // four fp32 arrays of qstride = b*h*d values each (lambda_K, z_K, lambda_V, z_V).
+    const float* qparams;
+    int64_t qstride;
 };
 
 constexpr int kMaxFix = 8;           // evicted rows the subtractive schedule handles
@@ -94,7 +98,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     constexpr int LPR = D / EPV;            // lanes per row
     constexpr int NW = NT / kWave;
     constexpr int NG = NT / LPR;            // row groups per workgroup
-    constexpr int ROWB = D * Elem<T>::kBytes;
+    constexpr int ROWB = D * Elem<T>::kBytes;          // one cache row
+    typedef typename Act<T>::type AT;
+    constexpr int XROWB = D * Elem<AT>::kBytes;        // one row of q, k_new, v_new, out
+    constexpr bool kQ8 = Elem<T>::kBytes == 1;
     constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
     constexpr int UF = SWA_UF;              // key+value row pairs per group and pipeline stage (fused pass)
     constexpr int UV = 4;                   // value rows in flight per group (gathered pass)
@@ -156,8 +163,25 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         char* Vp = a.v_cache + pair * (int64_t)cap * ROWB;
         float* Sp = a.score + pair * (int64_t)cap;
         int32_t* Pp = a.pos + pair * (int64_t)cap;
-        const char* knew = a.k_new + pair * ROWB;
-        const char* vnew = a.v_new + pair * ROWB;
+        const float* lamK = kQ8 ? a.qparams + pair * D : nullptr;
+        const float* zK = kQ8 ? lamK + a.qstride : nullptr;
+        const float* lamV = kQ8 ? lamK + 2 * a.qstride : nullptr;
+        const float* zV = kQ8 ? lamK + 3 * a.qstride : nullptr;
+        // This lane's 16 bytes of the new token's key and value rows, in the cache's format (with
+        // a compressed cache the row is quantised on arrival, so the step reads what memory will
+        // hold).  Wherever a loop meets slot `len` it takes these instead of what it loaded.
+        Vec16 nk, nv;
+        if constexpr (kQ8) {
+            nk = quantise16(a.k_new + pair * XROWB + sub * 32, lamK + sub * 16, zK + sub * 16);
+            nv = quantise16(a.v_new + pair * XROWB + sub * 32, lamV + sub * 16, zV + sub * 16);
+        } else {
+            nk = load16(a.k_new + pair * XROWB + sub * 16);
+            nv = load16(a.v_new + pair * XROWB + sub * 16);
+        }
+        auto write_out = [&](int e, float v) {
+            if constexpr (kQ8) v = lamV[e] * (v - zV[e]);      // accumulated in code space
+            store_elem<AT>(a.out + pair * XROWB, e, v);
+        };
 
         int w_eff = 0;
         budget(n, m, a.w, a.sparsity_bp, keep, n_local, n_global, w_eff);
@@ -195,17 +219,16 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         // ---- append (with fused compaction the new row goes straight to its final slot) ----
         if (!fc) {
             if (tid < LPR) {
-                store16(Kp + (int64_t)len * ROWB + tid * 16, load16(knew + tid * 16));
+                store16(Kp + (int64_t)len * ROWB + sub * 16, nk);
             } else if (tid < 2 * LPR) {
-                const int t2 = tid - LPR;
-                store16(Vp + (int64_t)len * ROWB + t2 * 16, load16(vnew + t2 * 16));
+                store16(Vp + (int64_t)len * ROWB + sub * 16, nv);
             }
             if (tid == 0) Pp[len] = n - 1;
         }
         if (tid == 0) s_ecnt = 0;
 
         QFrag<T> qf;
-        qf.load(load16(a.q + pair * ROWB + sub * 16));
+        qf.load(a.q + pair * XROWB, sub, lamK, zK);
 
         float Mg = -INFINITY;     // running max of this group's logits
         float Sg = 0.f;           // fused pass: running sum of exp(z - Mg)
@@ -223,16 +246,20 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 for (int u = 0; u < UF; ++u) {
                     int row = base + u * NG + grp;
                     row = row < m ? row : len;
-                    const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
-                    const char* vs = (row == len) ? vnew : Vp + (int64_t)row * ROWB;
-                    kv[u] = load16(ks + sub * 16);
-                    vv[u] = load16(vs + sub * 16);
+                    kv[u] = load16(Kp + (int64_t)row * ROWB + sub * 16);
+                    vv[u] = load16(Vp + (int64_t)row * ROWB + sub * 16);
                 }
             };
-            auto reduce_stage = [&](int base, const Vec16(&kv)[UF], const Vec16(&vv)[UF]) {
+            auto reduce_stage = [&](int base, Vec16(&kv)[UF], Vec16(&vv)[UF]) {
                 float z[UF];
 #pragma unroll
-                for (int u = 0; u < UF; ++u) z[u] = qf.dot(kv[u], 0.f);
+                for (int u = 0; u < UF; ++u) {
+                    if (base + u * NG + grp >= len) {      // slot len and the padding behind it
+                        kv[u] = nk;
+                        vv[u] = nv;
+                    }
+                    z[u] = qf.dot(kv[u], 0.f);
+                }
 #pragma unroll
                 for (int u = 0; u < UF; ++u) z[u] = group_sum<LPR>(z[u]) * a.scale;
                 float mc = -INFINITY;
@@ -298,11 +325,10 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 #pragma unroll
                 for (int u = 0; u < UK; ++u) {
                     const int row = base + u * NG + grp;
-                    if (row < m) {
-                        const char* ks = (row == len) ? knew : Kp + (int64_t)row * ROWB;
-                        kv[u] = load16(ks + sub * 16);
+                    if (row < len) {
+                        kv[u] = load16(Kp + (int64_t)row * ROWB + sub * 16);
                     } else {
-                        kv[u] = Vec16{0u, 0u, 0u, 0u};
+                        kv[u] = nk;
                     }
                 }
 #pragma unroll
@@ -674,10 +700,11 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 int idx = s_evict[k];
                 idx = idx < 0 ? 0 : (idx > len ? len : idx);
                 const float pw = s_p[idx];
-                const char* vs = (idx >= stash_lo) ? s_stV + (idx - stash_lo) * ROWB
-                                                   : ((idx == len) ? vnew : Vp + (int64_t)idx * ROWB);
+                const char* vs = (idx >= stash_lo) ? s_stV + (idx - stash_lo) * ROWB : Vp + (int64_t)idx * ROWB;
+                Vec16 vr = load16(vs + sub * 16);
+                if (idx == len) vr = nv;
                 float f[EPV];
-                unpack<T>(load16(vs + sub * 16), f);
+                unpack<T>(vr, f);
 #pragma unroll
                 for (int e = 0; e < EPV; ++e) s_fix[k * D + sub * EPV + e] = pw * f[e];
             }
@@ -693,7 +720,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                 }
                 float t = At / St;
                 for (int k = 0; k < ec; ++k) t -= s_fix[k * D + e];
-                store_elem<T>(a.out + pair * ROWB, e, t / (1.f - pe));
+                write_out(e, t / (1.f - pe));
             }
         } else {
             // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i
@@ -711,8 +738,8 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                         int idx = src_of(j);
                         idx = idx < 0 ? 0 : (idx > len ? len : idx);
                         pw[u] = s_p[idx];
-                        const char* src = (idx == len) ? vnew : Vp + (int64_t)idx * ROWB;
-                        vv[u] = load16(src + sub * 16);
+                        vv[u] = load16(Vp + (int64_t)idx * ROWB + sub * 16);
+                        if (idx == len) vv[u] = nv;
                     } else {
                         pw[u] = 0.f;
                         vv[u] = Vec16{0u, 0u, 0u, 0u};
@@ -746,7 +773,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     pst += s_wS[v];
                     t += s_acc[v * D + e];
                 }
-                store_elem<T>(a.out + pair * ROWB, e, t / pst);
+                write_out(e, t / pst);
             }
         }
 
@@ -768,10 +795,9 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     const int dst = (jstar < len) ? jstar : len;
                     if (dst < keep) {
                         if (tid < LPR) {
-                            store16(Kp + (int64_t)dst * ROWB + tid * 16, load16(knew + tid * 16));
+                            store16(Kp + (int64_t)dst * ROWB + sub * 16, nk);
                         } else if (tid < 2 * LPR) {
-                            const int t2 = tid - LPR;
-                            store16(Vp + (int64_t)dst * ROWB + t2 * 16, load16(vnew + t2 * 16));
+                            store16(Vp + (int64_t)dst * ROWB + sub * 16, nv);
                         }
                     }
                 } else {
@@ -779,10 +805,12 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                         int src = s_movers[k], dst = s_holes[k];
                         src = src > len ? len : src;
                         dst = dst >= keep ? keep - 1 : dst;
-                        const char* ks = (src == len) ? knew : Kp + (int64_t)src * ROWB;
-                        const char* vs = (src == len) ? vnew : Vp + (int64_t)src * ROWB;
-                        const Vec16 kr = load16(ks + sub * 16);
-                        const Vec16 vr = load16(vs + sub * 16);
+                        Vec16 kr = load16(Kp + (int64_t)src * ROWB + sub * 16);
+                        Vec16 vr = load16(Vp + (int64_t)src * ROWB + sub * 16);
+                        if (src == len) {
+                            kr = nk;
+                            vr = nv;
+                        }
                         store16(Kp + (int64_t)dst * ROWB + sub * 16, kr);
                         store16(Vp + (int64_t)dst * ROWB + sub * 16, vr);
                     }
@@ -814,12 +842,14 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     if (j < keep) {
                         int src = src_of(j);
                         src = src < 0 ? 0 : (src > len ? len : src);
-                        const char* ks = (src >= stash_lo) ? s_stK + (src - stash_lo) * ROWB
-                                                           : ((src == len) ? knew : Kp + (int64_t)src * ROWB);
-                        const char* vs = (src >= stash_lo) ? s_stV + (src - stash_lo) * ROWB
-                                                           : ((src == len) ? vnew : Vp + (int64_t)src * ROWB);
+                        const char* ks = (src >= stash_lo) ? s_stK + (src - stash_lo) * ROWB : Kp + (int64_t)src * ROWB;
+                        const char* vs = (src >= stash_lo) ? s_stV + (src - stash_lo) * ROWB : Vp + (int64_t)src * ROWB;
                         kk[u] = load16(ks + sub * 16);
                         vv2[u] = load16(vs + sub * 16);
+                        if (src == len) {
+                            kk[u] = nk;
+                            vv2[u] = nv;
+                        }
                         dst[u] = j;
                     }
                 }
@@ -888,9 +918,11 @@ static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes,
 int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
                   void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
                   const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
-                  float* probs_dbg, void* workspace, hipStream_t stream)
+                  float* probs_dbg, void* workspace, const float* qparams, hipStream_t stream)
 {
     DecodeArgs a;
+    a.qparams = qparams;
+    a.qstride = (int64_t)p.b * p.h * p.d;
     a.q = static_cast<const char*>(q);
     a.k_new = static_cast<const char*>(k_new);
     a.v_new = static_cast<const char*>(v_new);
@@ -928,13 +960,16 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.stash_rows = (a.fuse_compaction && !a.unordered) ? decode_stash_rows(p) : 0;
 
     const int64_t pairs = (int64_t)p.b * p.h;
-    const int rowb = p.d * (p.dtype == SWA_F32 ? 4 : 2);
+    const int rowb = cache_row_bytes(p);
     const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? (a.unordered ? 20 : 16) : 8) +
                              (size_t)a.stash_rows * rowb * 2;
     const int nt = decode_block_threads(pairs, bound);
 
     auto launch = [&](const DecodeArgs& args) -> int {
-        if (p.dtype == SWA_F32) {
+        if (p.flags & SWA_KV_INT8) {
+            return p.d == 64 ? launch_decode_t<Q8, 64>(args, pairs, lds_bytes, nt, stream)
+                             : launch_decode_t<Q8, 128>(args, pairs, lds_bytes, nt, stream);
+        } else if (p.dtype == SWA_F32) {
             return p.d == 64 ? launch_decode_t<F32, 64>(args, pairs, lds_bytes, nt, stream)
                              : launch_decode_t<F32, 128>(args, pairs, lds_bytes, nt, stream);
         } else if (p.dtype == SWA_F16) {

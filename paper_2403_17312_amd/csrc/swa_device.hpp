@@ -20,6 +20,7 @@ constexpr int32_t kStatusCapacityBit = 1;
 struct F32 {};
 struct F16 {};
 struct BF16 {};
+struct Q8 {};   // cache rows hold 8-bit codes (Section V-B); queries, new rows and outputs are fp16
 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
@@ -48,6 +49,22 @@ template <>
 struct Elem<BF16> {
     static constexpr int kBytes = 2;
     static constexpr int kPerVec = 8;
+};
+
+template <>
+struct Elem<Q8> {
+    static constexpr int kBytes = 1;
+    static constexpr int kPerVec = 16;
+};
+
+// Type of the per-step rows (q, k_new, v_new, out) that go with a cache element type.
+template <typename T>
+struct Act {
+    typedef T type;
+};
+template <>
+struct Act<Q8> {
+    typedef F16 type;
 };
 
 __device__ __forceinline__ float u2f(uint32_t u) { return __builtin_bit_cast(float, u); }
@@ -91,6 +108,47 @@ __device__ __forceinline__ void unpack<BF16>(const Vec16& v, float* f)
     f[4] = bf16_lo(v.z); f[5] = bf16_hi(v.z); f[6] = bf16_lo(v.w); f[7] = bf16_hi(v.w);
 }
 
+template <>
+__device__ __forceinline__ void unpack<Q8>(const Vec16& v, float* f)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        f[4 * i + 0] = (float)(w[i] & 0xffu);
+        f[4 * i + 1] = (float)((w[i] >> 8) & 0xffu);
+        f[4 * i + 2] = (float)((w[i] >> 16) & 0xffu);
+        f[4 * i + 3] = (float)(w[i] >> 24);
+    }
+}
+
+// Section V-B: code = round(x / lambda + z), saturated to 8 bits.  One IEEE rounding per
+// operation (no reciprocal, no contraction), ties to even: the code is an integer decision and
+// has to come out the same wherever it is taken.
+__device__ __forceinline__ uint32_t quantise_one(float x, float lam, float z)
+{
+    float t = __fdiv_rn(x, lam);
+    t = __fadd_rn(t, z);
+    t = rintf(t);
+    t = t < 0.f ? 0.f : (t > 255.f ? 255.f : t);
+    return (uint32_t)t;
+}
+
+// Quantise 16 consecutive channels of an fp16 row (32 bytes at `src`) into one 16-byte code vector.
+__device__ __forceinline__ Vec16 quantise16(const char* src, const float* lam, const float* zero)
+{
+    float f[16];
+    unpack<F16>(*reinterpret_cast<const Vec16*>(src), f);
+    unpack<F16>(*reinterpret_cast<const Vec16*>(src + 16), f + 8);
+    uint32_t w[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        w[i] = 0u;
+#pragma unroll
+        for (int k = 0; k < 4; ++k) w[i] |= quantise_one(f[4 * i + k], lam[4 * i + k], zero[4 * i + k]) << (8 * k);
+    }
+    return Vec16{w[0], w[1], w[2], w[3]};
+}
+
 // Partial dot product of one 16-byte key vector with the matching query vector,
 // fp32 accumulation.  Query operand: the raw vector for F16 (packed dot), the
 // widened fp32 values otherwise.
@@ -99,7 +157,10 @@ struct QFrag;
 template <>
 struct QFrag<F32> {
     float f[4];
-    __device__ __forceinline__ void load(const Vec16& v) { unpack<F32>(v, f); }
+    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
+    {
+        unpack<F32>(*reinterpret_cast<const Vec16*>(qrow + sub * 16), f);
+    }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         acc = __builtin_fmaf(u2f(k.x), f[0], acc);
@@ -112,7 +173,10 @@ struct QFrag<F32> {
 template <>
 struct QFrag<F16> {
     Vec16 raw;
-    __device__ __forceinline__ void load(const Vec16& v) { raw = v; }
+    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
+    {
+        raw = *reinterpret_cast<const Vec16*>(qrow + sub * 16);
+    }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         // v_dot2_f32_f16: exact fp16 products, fp32 accumulation
@@ -126,7 +190,10 @@ struct QFrag<F16> {
 template <>
 struct QFrag<BF16> {
     float f[8];
-    __device__ __forceinline__ void load(const Vec16& v) { unpack<BF16>(v, f); }
+    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
+    {
+        unpack<BF16>(*reinterpret_cast<const Vec16*>(qrow + sub * 16), f);
+    }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         acc = __builtin_fmaf(bf16_lo(k.x), f[0], acc);
@@ -137,6 +204,35 @@ struct QFrag<BF16> {
         acc = __builtin_fmaf(bf16_hi(k.z), f[5], acc);
         acc = __builtin_fmaf(bf16_lo(k.w), f[6], acc);
         acc = __builtin_fmaf(bf16_hi(k.w), f[7], acc);
+        return acc;
+    }
+};
+
+// Compressed keys: q . k = sum_c q_c lambda_c (code_c - z_c), so the query is scaled by the
+// channel's lambda once and the zero-point term becomes a per-lane constant; the inner loop is
+// one convert and one FMA per code.
+template <>
+struct QFrag<Q8> {
+    float f[16];
+    float c0;
+    __device__ __forceinline__ void load(const char* qrow, int sub, const float* lam, const float* zero)
+    {
+        unpack<F16>(*reinterpret_cast<const Vec16*>(qrow + sub * 32), f);
+        unpack<F16>(*reinterpret_cast<const Vec16*>(qrow + sub * 32 + 16), f + 8);
+        c0 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            f[i] *= lam[sub * 16 + i];
+            c0 = __builtin_fmaf(-f[i], zero[sub * 16 + i], c0);
+        }
+    }
+    __device__ __forceinline__ float dot(const Vec16& k, float acc) const
+    {
+        float c[16];
+        unpack<Q8>(k, c);
+        acc += c0;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc = __builtin_fmaf(c[i], f[i], acc);
         return acc;
     }
 };
@@ -201,7 +297,7 @@ __device__ __forceinline__ float dpp_move(float v)
     return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xf, 0xf, true));
 }
 
-// Sum over aligned groups of LANES consecutive lanes (8, 16 or 32); every lane of the
+// Sum over aligned groups of LANES consecutive lanes (4, 8, 16 or 32); every lane of the
 // group gets the total.  quad_perm swaps (xor 1, xor 2), then mirrors within 8 and
 // within 16 lanes; only the 32-lane case needs one LDS-routed exchange.
 template <int LANES>
@@ -209,7 +305,7 @@ __device__ __forceinline__ float group_sum(float v)
 {
     v += dpp_move<0xB1>(v);    // quad_perm [1,0,3,2]
     v += dpp_move<0x4E>(v);    // quad_perm [2,3,0,1]
-    v += dpp_move<0x141>(v);   // row_half_mirror
+    if (LANES >= 8) v += dpp_move<0x141>(v);   // row_half_mirror
     if (LANES >= 16) v += dpp_move<0x140>(v);   // row_mirror
     if (LANES >= 32) v += __shfl_xor(v, 16, 64);
     return v;

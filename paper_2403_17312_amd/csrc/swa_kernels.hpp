@@ -20,6 +20,12 @@ int decode_block_threads(int64_t pairs, int len_bound);
 // first launch to its second (present only when SWA_HEAD_SHARED is set).
 size_t shared_workspace_offset(const swa_params& p);
 
+// Bytes of one cache row.
+inline int cache_row_bytes(const swa_params& p)
+{
+    return (p.flags & SWA_KV_INT8) ? p.d : p.d * (p.dtype == SWA_F32 ? 4 : 2);
+}
+
 // Rows of K and V the fused-compaction decode parks in LDS (0 = none).
 int decode_stash_rows(const swa_params& p);
 
@@ -28,7 +34,12 @@ int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stre
 int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
                   void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
                   const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
-                  float* probs_dbg, void* workspace, hipStream_t stream);
+                  float* probs_dbg, void* workspace, const float* qparams, hipStream_t stream);
+
+// Channel-wise 8-bit compression of an fp16 cache (Section V-B): parameters from the cached rows,
+// then the codes.  qparams: four fp32 arrays of b*h*d values (lambda_K, z_K, lambda_V, z_V).
+int launch_quantize(const swa_params& p, const void* k_cache, const void* v_cache, const int32_t* cache_len,
+                    void* k_codes, void* v_codes, float* qparams, hipStream_t stream);
 
 int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* score, int32_t* pos,
                    const int32_t* kept_idx, const int32_t* kept_cnt, int32_t* cache_len,

@@ -81,7 +81,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
                  prompt: Optional[dict] = None, verbose: bool = False,
                  use_len_bound: bool = False, fused: bool = False, unordered: bool = False,
-                 sparsity_of_step=None, head_shared: bool = False) -> Report:
+                 sparsity_of_step=None, head_shared: bool = False, kv_int8: bool = False) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
@@ -127,6 +127,31 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
     else:
         st.score.zero_()
 
+    qp = None
+    if kv_int8:
+        # Section V-B: the cache is compressed once the prompt (and its importance seed) is done.
+        # Parameters and codes must equal the oracle's bit for bit; from here on the oracle's cache
+        # holds the de-quantised values, which are what the compressed attention reads.
+        st.quantize()
+        qp_g = [_sub(st.qparams[k], seqs_t, heads_t).cpu().numpy() for k in range(4)]
+        lamK, zK = O.kv_qparams(K_o, len_o)
+        lamV, zV = O.kv_qparams(V_o, len_o)
+        for g, o, nm in zip(qp_g, (lamK, zK, lamV, zV), ("lambda_K", "z_K", "lambda_V", "z_V")):
+            assert np.array_equal(g, o), f"quantisation parameter {nm}"
+        cK, cV = O.kv_quantize(K_o, len_o, lamK, zK), O.kv_quantize(V_o, len_o, lamV, zV)
+        cK_g = _sub(st.K, seqs_t, heads_t).cpu().numpy()
+        cV_g = _sub(st.V, seqs_t, heads_t).cpu().numpy()
+        for i, L in enumerate(len_o):
+            assert np.array_equal(cK_g[i, :, :L], cK[i, :, :L]), "key codes"
+            assert np.array_equal(cV_g[i, :, :L], cV[i, :, :L]), "value codes"
+        K_o, V_o = O.kv_dequantize(cK, len_o, lamK, zK), O.kv_dequantize(cV, len_o, lamV, zV)
+        qp = (lamK, zK, lamV, zV)
+        ones = np.ones_like(len_o)
+
+        def through_codes(x, lam, zero):          # [S,H,d] new rows: quantise on arrival, de-quantise
+            x4 = np.ascontiguousarray(x[:, :, None, :])
+            return O.kv_dequantize(O.kv_quantize(x4, ones, lam, zero), ones, lam, zero)[:, :, 0, :]
+
     host_len = list(prompt["lengths"])          # host-side replay of every sequence's length
     for t in range(steps):
         q, kn, vn = W.make_step(wl, t, prompt["mu"])
@@ -152,6 +177,8 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
 
         # ---- oracle step from the adopted state ---------------------------------
         q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
+        if kv_int8:
+            kn_o, vn_o = through_codes(kn_o, qp[0], qp[1]), through_codes(vn_o, qp[2], qp[3])
         kept_o, cnt_o, out_o, p_o = O.decode_step(q_o, kn_o, vn_o, K_o, V_o, score_o, pos_o, len_o,
                                                   n_o, wl.w, sp_t, wl.scale, head_shared=head_shared)
         kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
@@ -261,8 +288,13 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             O.compact(K_o, V_o, score_o, pos_o, kept_g, cnt_g, len_o)
             assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o)
             if do_check:
-                K_g = _np64(_sub(st.K, seqs_t, heads_t))
-                V_g = _np64(_sub(st.V, seqs_t, heads_t))
+                if kv_int8:
+                    capc = np.full_like(len_o, st.K.shape[2])
+                    K_g = O.kv_dequantize(_sub(st.K, seqs_t, heads_t).cpu().numpy(), capc, qp[0], qp[1])
+                    V_g = O.kv_dequantize(_sub(st.V, seqs_t, heads_t).cpu().numpy(), capc, qp[2], qp[3])
+                else:
+                    K_g = _np64(_sub(st.K, seqs_t, heads_t))
+                    V_g = _np64(_sub(st.V, seqs_t, heads_t))
                 s_g = _np64(_sub(st.score, seqs_t, heads_t))
                 pos_g = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
                 if unordered:

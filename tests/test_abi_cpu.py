@@ -22,7 +22,7 @@ def B():
 def _declared_functions():
     text = open(os.path.join(ROOT, "include", "swa.h")).read()
     text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
-    return sorted(set(re.findall(r"\b(swa_[a-z_]+)\s*\(", text)))
+    return sorted(set(re.findall(r"\b(swa_[a-z0-9_]+)\s*\(", text)))
 
 
 def test_library_exports_every_declared_symbol(B):
@@ -91,7 +91,8 @@ def test_workspace_bytes(B):
     (dict(flags=2), "SWA_ERR_BAD_SHAPE"),          # SWA_UNORDERED needs SWA_FUSE_COMPACTION
     (dict(flags=4), "SWA_ERR_BAD_SHAPE"),          # SWA_HEAD_SHARED needs the other two
     (dict(flags=5), "SWA_ERR_BAD_SHAPE"),
-    (dict(flags=8), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=16), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=8), "SWA_ERR_UNSUPPORTED_DTYPE"),  # SWA_KV_INT8 goes with fp16 rows only
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),
     (dict(scale=float("nan")), "SWA_ERR_BAD_SHAPE"),
@@ -138,6 +139,29 @@ def test_null_and_misaligned_pointers_are_rejected(B):
     assert L.swa_prefill_scores(ctypes.byref(p), ok, 0, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
     assert L.swa_prefill_scores(ctypes.byref(p), ok, 129, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
     assert L.swa_prefill_scores(ctypes.byref(p), None, 4, ok, ok, ok, ok, ok) == B.SWA_ERR_NULL
+
+
+def test_compressed_cache_entry_points_validate_their_arguments(B):
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    p16 = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16)
+    pq = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=B.SWA_KV_INT8)
+    p32 = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F32)
+    # the plain step refuses a compressed cache, the compressed step a plain one
+    assert L.swa_decode_step(ctypes.byref(pq), *([ok] * 15)) == B.SWA_ERR_UNSUPPORTED_DTYPE
+    assert L.swa_decode_step_q8(ctypes.byref(p16), *([ok] * 16)) == B.SWA_ERR_UNSUPPORTED_DTYPE
+    a = [ok] * 16
+    a[5] = None                                               # the quantisation parameters
+    assert L.swa_decode_step_q8(ctypes.byref(pq), *a) == B.SWA_ERR_NULL
+    a = [ok] * 16
+    a[3] = ctypes.c_void_p(0x1004)
+    assert L.swa_decode_step_q8(ctypes.byref(pq), *a) == B.SWA_ERR_ALIGNMENT
+    assert L.swa_quantize_kv(ctypes.byref(p32), *([ok] * 7)) == B.SWA_ERR_UNSUPPORTED_DTYPE
+    for i in range(6):
+        a = [ok] * 7
+        a[i] = None
+        assert L.swa_quantize_kv(ctypes.byref(p16), *a) == B.SWA_ERR_NULL, i
+    assert L.swa_quantize_kv(None, *([ok] * 7)) == B.SWA_ERR_NULL
 
 
 def test_binding_fails_loudly_without_the_library(B, monkeypatch, tmp_path):

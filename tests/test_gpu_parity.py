@@ -188,6 +188,31 @@ def test_head_shared_selection_matches_the_oracle(env):
     assert torch.equal(srt, srt[:, :1].expand_as(srt))
 
 
+def test_kv_int8_compressed_cache_matches_the_oracle(env):
+    # Section V-B: 8-bit channel-wise codes in memory; parameters and codes bit-exact, the step
+    # against the oracle on the de-quantised values, in every way the step can be issued
+    O, B, W, LS = env
+    _say("compressed cache, small shapes")
+    for d, w, modes in [(128, 7, ("unordered", "fused", "split")), (64, 3, ("unordered", "split"))]:
+        wl = W.Workload(f"t_q8_d{d}", 37, b=3, h=3, d=d, dtype="f16", prompt_lo=1, prompt_hi=300,
+                        steps=14, w=w, sparsity_bp=7500, hh_frac=0.02, prefill_R=6)
+        for mode in modes:
+            _say(f"  d={d} {mode}")
+            rep = LS.run_lockstep(wl, fused=mode != "split", unordered=mode == "unordered", kv_int8=True)
+            assert rep.evictions > 0
+    wl = W.Workload("t_q8_shared", 38, b=2, h=4, d=128, dtype="f16", prompt_lo=40, prompt_hi=200,
+                    steps=10, w=SW_EVEN(B), sparsity_bp=6000, hh_frac=0.02)
+    LS.run_lockstep(wl, fused=True, unordered=True, head_shared=True, kv_int8=True)
+    _say("compressed cache, config 2 at full size, every pair")
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], fused=True, unordered=True, kv_int8=True, use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+
+
+def SW_EVEN(B):
+    return B.SWA_W_EVEN_SPLIT
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
