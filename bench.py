@@ -53,7 +53,7 @@ def simulate_lengths(B, wl, lens):
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
-    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused):
+    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused, kv_int8=False):
         self.fused = bool(fused)
         flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
                  "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED,
@@ -69,19 +69,36 @@ class Replica:
         base = prompt["cache_len"].to(torch.int32)
         self.seq_lens = torch.stack([base + (t + 1) for t in range(wl.steps)]).contiguous()  # [T, b]
         # per-step params: the host knows an upper bound on the cached length of every step
+        self.kv_int8 = kv_int8
+        qf = B.SWA_KV_INT8 if kv_int8 else 0
         self.params = [B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype,
-                                     len_bound=lb, flags=flags) for lb in len_bounds]
+                                     len_bound=lb, flags=flags | qf) for lb in len_bounds]
+
+    def finish_prompt(self, q_tail):
+        """End of the prompt: importance seed (if the workload has one), then KV compression."""
+        if q_tail is not None:
+            self.st.prefill_scores(q_tail)
+        if self.kv_int8:
+            self.st.quantize()
 
     def decode(self, B, t, q, kn, vn):
         st = self.st
         if self.fused:
             # one kernel: the new lengths come back in kept_cnt, so the two arrays alternate
-            B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
-                              self.seq_lens[t], None, st.kept_cnt, st.out, None, st.workspace)
+            self._call(B, t, q, kn, vn, None)
             st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
         else:
+            self._call(B, t, q, kn, vn, st.kept_idx)
+
+    def _call(self, B, t, q, kn, vn, kept_idx):
+        st = self.st
+        if self.kv_int8:
+            B.swa_decode_step_q8(self.params[t], q, kn, vn, st.K, st.V, st.qparams, st.score, st.pos,
+                                 st.cache_len, self.seq_lens[t], kept_idx, st.kept_cnt, st.out, None,
+                                 st.workspace)
+        else:
             B.swa_decode_step(self.params[t], q, kn, vn, st.K, st.V, st.score, st.pos, st.cache_len,
-                              self.seq_lens[t], st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+                              self.seq_lens[t], kept_idx, st.kept_cnt, st.out, None, st.workspace)
 
     def compact(self, B, t):
         st = self.st
@@ -94,7 +111,7 @@ class Replica:
         self.compact(B, t)
 
 
-def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True):
+def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True, kv_int8=False):
     dev = "cuda"
     T = wl.steps
     R = max(1, math.ceil(steps / T))
@@ -107,11 +124,13 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     len_bounds = [max(m_t) for m_t in ms]
 
     def fresh(n):
-        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused) for _ in range(n)]
-        if q_tail is not None:
-            for r in reps:
-                r.st.prefill_scores(q_tail)
+        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8) for _ in range(n)]
+        for r in reps:
+            r.finish_prompt(q_tail)
         return reps
+
+    def abp(m, k):
+        return W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k, kv_int8)
 
     def run(reps, count):
         n = len(reps)
@@ -130,7 +149,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     # -------- prefill seed timing (separate from the decode metric)
     prefill_ms = None
     if q_tail is not None:
-        tmp = fresh(1)[0]
+        tmp = Replica(B, W, wl, prompt, torch, len_bounds, fused, False)
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record()
@@ -139,6 +158,20 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         torch.cuda.synchronize()
         prefill_ms = e0.elapsed_time(e1)
         del tmp
+    quantize_ms = None
+    if kv_int8:
+        tmp = Replica(B, W, wl, prompt, torch, len_bounds, fused, False).st
+        ck, cv = torch.zeros_like(tmp.K, dtype=torch.uint8), torch.zeros_like(tmp.V, dtype=torch.uint8)
+        qp = torch.zeros((4, wl.b, wl.h, wl.d), dtype=torch.float32, device=dev)
+        B.swa_quantize_kv(tmp.params, tmp.K, tmp.V, tmp.cache_len, ck, cv, qp)       # warm
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        B.swa_quantize_kv(tmp.params, tmp.K, tmp.V, tmp.cache_len, ck, cv, qp)
+        e1.record()
+        torch.cuda.synchronize()
+        quantize_ms = e0.elapsed_time(e1)
+        del tmp, ck, cv, qp
 
     # -------- timed region: exactly `steps` steps
     reps = fresh(R)
@@ -175,7 +208,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         t = i // R
         kv_tokens += sum(ms[t])
         for m, k in zip(ms[t], keeps[t]):
-            alg_bytes += wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+            alg_bytes += wl.h * abp(m, k)
 
     res = {
         "workload": wl.name, "steps": steps, "replicas": R, "mode": mode, "fused": fused,
@@ -184,7 +217,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         "generated_tokens_per_s": wl.b * steps / (total_ms * 1e-3),
         "alg_bytes_per_step": alg_bytes / steps,
         "alg_gbs_whole_step": alg_bytes / (total_ms * 1e-3) / 1e9,
-        "prefill_seed_ms": prefill_ms,
+        "prefill_seed_ms": prefill_ms, "quantize_kv_ms": quantize_ms,
     }
 
     # -------- per-kernel durations with HIP events on the launch stream (separate pass)
@@ -218,11 +251,11 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         steady = [dec[i] for i in range(steps) if i // n > 0]
         res["decode_first_step_ms"] = sum(first) / max(1, len(first))
         res["decode_steady_ms"] = sum(steady) / max(1, len(steady)) if steady else None
-        first_bytes = sum(wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+        first_bytes = sum(wl.h * abp(m, k)
                           for m, k in zip(ms[0], keeps[0]))
         res["decode_first_step_gbs"] = first_bytes / (res["decode_first_step_ms"] * 1e-3) / 1e9
         if steady:
-            sb = [sum(wl.h * W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k)
+            sb = [sum(wl.h * abp(m, k)
                       for m, k in zip(ms[i // n], keeps[i // n])) for i in range(steps) if i // n > 0]
             res["decode_steady_gbs"] = sum(sb) / (sum(steady) * 1e-3) / 1e9
         del reps
@@ -298,6 +331,9 @@ def main():
                          "step, compaction fills holes (SWA_UNORDERED); shared: unordered with one token set per "
                          "sequence from the head-summed importance (SWA_HEAD_SHARED, two launches); "
                          "split: swa_decode_step + swa_compact_kv")
+    ap.add_argument("--kv-int8", action="store_true",
+                    help="compress the cache to 8-bit channel-wise codes after the prompt (swa_quantize_kv) "
+                         "and step with swa_decode_step_q8 (fp16 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -321,7 +357,7 @@ def main():
     steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
     warmup = args.warmup if args.warmup is not None else wl.steps
     fused = args.step_mode if args.step_mode != "split" else False
-    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused)
+    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8)
 
     # Average launch duration of the dominant kernel.  Fused mode: the step IS one kernel, so the
     # HIP-event time of the graph replay divided by the number of launches is that kernel's
@@ -329,7 +365,7 @@ def main():
     # rocprofv3's per-kernel average (profiles/).  Split mode: per-launch event brackets.
     dec_ms = res["ms_per_step"] if fused else res["decode_kernel_ms_avg"]
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
-    traffic = load_traffic(wl.name) if args.step_mode == "unordered" else None
+    traffic = load_traffic(wl.name) if args.step_mode == "unordered" and not args.kv_int8 else None
     line = {
         "metric": "SWA decode-step KV tokens/s",
         "value": res["kv_tokens_per_s"],
@@ -337,7 +373,7 @@ def main():
         "n_gpus": 1, "steps": steps, "warmup": warmup,
         "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": wl.dtype, "data": "synthetic",
+        "dtype": wl.dtype + ("+u8kv" if args.kv_int8 else ""), "data": "synthetic",
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
                    "replicas": res["replicas"], "launch": args.mode,
@@ -360,7 +396,7 @@ def main():
         "generated_tokens_per_s": res["generated_tokens_per_s"],
         "detail": {k: res[k] for k in ("decode_kernel_ms_avg", "compact_kernel_ms_avg", "decode_first_step_ms",
                                        "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
-                                       "prefill_seed_ms")},
+                                       "prefill_seed_ms", "quantize_kv_ms")},
     }
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)
@@ -369,7 +405,9 @@ def main():
     for name in [x for x in args.others.split(",") if x and x != args.config]:
         o = W.CONFIGS[name]
         k = o.steps * max(1, 256 // o.steps)
-        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused)
+        if args.kv_int8 and o.dtype != "f16":
+            continue
+        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8)
         a = r["alg_bytes_per_step"] / ((r["ms_per_step"] if fused else r["decode_kernel_ms_avg"]) * 1e-3) / 1e9
         others.append({"workload": name, "steps": k, "kv_tokens_per_s": r["kv_tokens_per_s"],
                        "ms_per_step": r["ms_per_step"], "decode_kernel_ms_avg": r["decode_kernel_ms_avg"],

@@ -141,6 +141,9 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
     __shared__ float s_fix[kMaxFix * D];
     __shared__ int32_t s_evict[kMaxFix];
     __shared__ int32_t s_ecnt;
+    __shared__ __align__(16) unsigned char s_newc[kQ8 ? 2 * D : 16];   // codes of the new K and V rows
+    __shared__ __align__(16) float s_qs[kQ8 ? D : 4];
+    __shared__ __align__(16) float s_qz[kQ8 ? D : 4];
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -167,17 +170,46 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         const float* zK = kQ8 ? lamK + a.qstride : nullptr;
         const float* lamV = kQ8 ? lamK + 2 * a.qstride : nullptr;
         const float* zV = kQ8 ? lamK + 3 * a.qstride : nullptr;
-        // This lane's 16 bytes of the new token's key and value rows, in the cache's format (with
-        // a compressed cache the row is quantised on arrival, so the step reads what memory will
-        // hold).  Wherever a loop meets slot `len` it takes these instead of what it loaded.
+        // This lane's 16 bytes of the new token's key and value rows, in the cache's format, and
+        // its query operand.  Wherever a loop meets slot `len` it takes nk/nv instead of what it
+        // loaded.  With a compressed cache the new row is quantised on arrival (the step reads
+        // what memory will hold): one thread per channel loads the parameters, quantises and
+        // pre-scales the query (q_c lambda_c, and its zero-point product) into LDS, and the
+        // lanes pick their 16-channel pieces up from there in new_row_ready(), which every
+        // path calls once, after its first cache loads are in flight.
         Vec16 nk, nv;
+        QFrag<T> qf;
+        float pq = 0.f, pl = 0.f, pz = 0.f, pkn = 0.f, pvn = 0.f, plv = 0.f, pzv = 0.f;
         if constexpr (kQ8) {
-            nk = quantise16(a.k_new + pair * XROWB + sub * 32, lamK + sub * 16, zK + sub * 16);
-            nv = quantise16(a.v_new + pair * XROWB + sub * 32, lamV + sub * 16, zV + sub * 16);
+            if (tid < D) {
+                pl = lamK[tid];
+                pz = zK[tid];
+                plv = lamV[tid];
+                pzv = zV[tid];
+                pq = (float)reinterpret_cast<const _Float16*>(a.q + pair * XROWB)[tid];
+                pkn = (float)reinterpret_cast<const _Float16*>(a.k_new + pair * XROWB)[tid];
+                pvn = (float)reinterpret_cast<const _Float16*>(a.v_new + pair * XROWB)[tid];
+            }
         } else {
             nk = load16(a.k_new + pair * XROWB + sub * 16);
             nv = load16(a.v_new + pair * XROWB + sub * 16);
+            qf.load(load16(a.q + pair * XROWB + sub * 16));
         }
+        auto new_row_ready = [&]() {
+            if constexpr (kQ8) {
+                if (tid < D) {
+                    s_newc[tid] = (unsigned char)quantise_one(pkn, pl, pz);
+                    s_newc[D + tid] = (unsigned char)quantise_one(pvn, plv, pzv);
+                    const float qs = pq * pl;
+                    s_qs[tid] = qs;
+                    s_qz[tid] = qs * pz;
+                }
+                __syncthreads();
+                nk = *reinterpret_cast<const Vec16*>(s_newc + sub * 16);
+                nv = *reinterpret_cast<const Vec16*>(s_newc + D + sub * 16);
+                qf.load(s_qs + sub * 16, s_qz + sub * 16);
+            }
+        };
         auto write_out = [&](int e, float v) {
             if constexpr (kQ8) v = lamV[e] * (v - zV[e]);      // accumulated in code space
             store_elem<AT>(a.out + pair * XROWB, e, v);
@@ -218,6 +250,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
 
         // ---- append (with fused compaction the new row goes straight to its final slot) ----
         if (!fc) {
+            new_row_ready();
             if (tid < LPR) {
                 store16(Kp + (int64_t)len * ROWB + sub * 16, nk);
             } else if (tid < 2 * LPR) {
@@ -227,8 +260,6 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         }
         if (tid == 0) s_ecnt = 0;
 
-        QFrag<T> qf;
-        qf.load(a.q + pair * XROWB, sub, lamK, zK);
 
         float Mg = -INFINITY;     // running max of this group's logits
         float Sg = 0.f;           // fused pass: running sum of exp(z - Mg)
@@ -294,6 +325,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             };
             Vec16 kA[UF], vA[UF], kB[UF], vB[UF];
             load_stage(0, kA, vA);
+            if (fc) new_row_ready();
             for (int base = 0; base < m; base += 2 * STEP) {
                 load_stage(base + STEP, kB, vB);
                 reduce_stage(base, kA, vA);
@@ -320,6 +352,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
             }
         } else {
             // ---- key-only pass -------------------------------------------------------
+            if (fc) new_row_ready();
             for (int base = 0; base < m; base += NG * UK) {
                 Vec16 kv[UK];
 #pragma unroll
@@ -444,6 +477,7 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
         }
         } else {
             // ---- phase 2 of the head-shared step: reload what phase 1 published --------------
+            new_row_ready();
             if (tid == 0) s_ecnt = 0;
             const float* Pw = a.ws_p + pair * (int64_t)cap;
             const float* Sn = a.ws_snew + pair * (int64_t)cap;
@@ -465,8 +499,9 @@ __global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
                     }
                 }
             }
-            // the dense output stands in for the wave partials of the streaming pass
-            for (int e = tid; e < D; e += NT) s_acc[e] = fused ? a.ws_abar[pair * D + e] : 0.f;
+            // the dense output stands in for wave 0's partial of the streaming pass; the other
+            // waves' partials are empty (weight 0, so their sums must be finite: zero)
+            for (int e = tid; e < NW * D; e += NT) s_acc[e] = (fused && e < D) ? a.ws_abar[pair * D + e] : 0.f;
             if (tid < 16) {
                 s_redA[tid] = (tid == 0) ? 0.f : -INFINITY;
                 s_wS[tid] = (tid == 0) ? 1.f : 0.f;

@@ -133,22 +133,6 @@ __device__ __forceinline__ uint32_t quantise_one(float x, float lam, float z)
     return (uint32_t)t;
 }
 
-// Quantise 16 consecutive channels of an fp16 row (32 bytes at `src`) into one 16-byte code vector.
-__device__ __forceinline__ Vec16 quantise16(const char* src, const float* lam, const float* zero)
-{
-    float f[16];
-    unpack<F16>(*reinterpret_cast<const Vec16*>(src), f);
-    unpack<F16>(*reinterpret_cast<const Vec16*>(src + 16), f + 8);
-    uint32_t w[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-        w[i] = 0u;
-#pragma unroll
-        for (int k = 0; k < 4; ++k) w[i] |= quantise_one(f[4 * i + k], lam[4 * i + k], zero[4 * i + k]) << (8 * k);
-    }
-    return Vec16{w[0], w[1], w[2], w[3]};
-}
-
 // Partial dot product of one 16-byte key vector with the matching query vector,
 // fp32 accumulation.  Query operand: the raw vector for F16 (packed dot), the
 // widened fp32 values otherwise.
@@ -157,10 +141,7 @@ struct QFrag;
 template <>
 struct QFrag<F32> {
     float f[4];
-    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
-    {
-        unpack<F32>(*reinterpret_cast<const Vec16*>(qrow + sub * 16), f);
-    }
+    __device__ __forceinline__ void load(const Vec16& v) { unpack<F32>(v, f); }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         acc = __builtin_fmaf(u2f(k.x), f[0], acc);
@@ -173,10 +154,7 @@ struct QFrag<F32> {
 template <>
 struct QFrag<F16> {
     Vec16 raw;
-    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
-    {
-        raw = *reinterpret_cast<const Vec16*>(qrow + sub * 16);
-    }
+    __device__ __forceinline__ void load(const Vec16& v) { raw = v; }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         // v_dot2_f32_f16: exact fp16 products, fp32 accumulation
@@ -190,10 +168,7 @@ struct QFrag<F16> {
 template <>
 struct QFrag<BF16> {
     float f[8];
-    __device__ __forceinline__ void load(const char* qrow, int sub, const float*, const float*)
-    {
-        unpack<BF16>(*reinterpret_cast<const Vec16*>(qrow + sub * 16), f);
-    }
+    __device__ __forceinline__ void load(const Vec16& v) { unpack<BF16>(v, f); }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
         acc = __builtin_fmaf(bf16_lo(k.x), f[0], acc);
@@ -215,15 +190,14 @@ template <>
 struct QFrag<Q8> {
     float f[16];
     float c0;
-    __device__ __forceinline__ void load(const char* qrow, int sub, const float* lam, const float* zero)
+    // qs[c] = q_c lambda_c and qz[c] = q_c lambda_c z_c for this lane's 16 channels
+    __device__ __forceinline__ void load(const float* qs, const float* qz)
     {
-        unpack<F16>(*reinterpret_cast<const Vec16*>(qrow + sub * 32), f);
-        unpack<F16>(*reinterpret_cast<const Vec16*>(qrow + sub * 32 + 16), f + 8);
         c0 = 0.f;
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-            f[i] *= lam[sub * 16 + i];
-            c0 = __builtin_fmaf(-f[i], zero[sub * 16 + i], c0);
+            f[i] = qs[i];
+            c0 -= qz[i];
         }
     }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const

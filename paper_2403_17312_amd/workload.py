@@ -178,13 +178,17 @@ def make_step(wl: Workload, t: int, mu: torch.Tensor):
     return q, k_new, v_new
 
 
-def algorithmic_bytes_per_pair(d: int, elem_bytes: int, m: int, keep: int) -> int:
+def algorithmic_bytes_per_pair(d: int, elem_bytes: int, m: int, keep: int, kv_int8: bool = False) -> int:
     """Bytes one (sequence, head) pair must move in one decode step.
 
     m key rows + keep value rows + importance read and write over m slots + the
     four per-step rows (q, k_new, v_new, out) + the kept-index list.  With fp16,
     one layer's K plus V of one token over all heads is 4 * hidden bytes, the
-    per-token figure of the paper's caching-time model (Section V-A).
+    per-token figure of the paper's caching-time model (Section V-A).  With the
+    8-bit compressed cache of Section V-B a cache row is d bytes, the per-step
+    rows stay fp16, and the pair's four fp32 parameter rows are read as well.
     """
+    if kv_int8:
+        return d * m + d * keep + 8 * m + 4 * (2 * d) + 4 * (4 * d) + 4 * keep
     row = d * elem_bytes
     return row * m + row * keep + 8 * m + 4 * row + 4 * keep

@@ -68,7 +68,7 @@ def new_state(wl: W.Workload, prompt: dict, debug_probs: bool = True) -> B.Decod
 def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
     atol, rel_elem, rtol = TOL[dtype]
     err = np.abs(out_gpu - out_ref)
-    assert np.all(np.isfinite(out_gpu)), what
+    assert np.all(np.isfinite(out_gpu)), f"{what}: non-finite output at {np.argwhere(~np.isfinite(out_gpu))[:8].tolist()}"
     rel = np.linalg.norm(out_gpu - out_ref, axis=-1) / np.maximum(np.linalg.norm(out_ref, axis=-1), 1e-30)
     excess = err - (atol + rel_elem * np.abs(out_ref))
     assert excess.max() <= 0, f"{what}: max abs {err.max():.3e} exceeds {atol} + {rel_elem:.2e}*|ref|"
