@@ -53,7 +53,7 @@ int decode_stash_rows(const swa_params& p)
     return rows;
 }
 
-int decode_block_threads(int64_t pairs, int len_bound)
+int decode_block_threads(int64_t pairs, int len_bound, bool kv_int8)
 {
     // Tuning override (128, 256 or 512), read once.
     static const int forced = [] {
@@ -65,8 +65,10 @@ int decode_block_threads(int64_t pairs, int len_bound)
     // Measured on MI355X (all five workloads): caches of a thousand slots and more (the first
     // step after a prompt, low sparsity) want 512 threads per pair, shorter ones 256; the pair
     // count matters little.
-    (void)pairs;
-    return len_bound >= 1024 ? 512 : 256;
+    if (!kv_int8) return len_bound >= 1024 ? 512 : 256;
+    // 8-bit rows are half as long, so a workgroup has half the lanes' worth of work per row and
+    // the fixed phases weigh more: smaller workgroups, more of them in flight.
+    return (pairs >= 1024 && len_bound < 1024) ? 128 : 256;
 }
 
 __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)

@@ -91,8 +91,11 @@ __device__ __forceinline__ void merge_acc(float& M, float& S, float* acc, float 
     M = Mn;
 }
 
+// Register budget: five waves per SIMD (96 VGPRs) for the 16- and 32-bit caches, four (128) for
+// the 8-bit one, whose lanes carry 16 channels each; neither bound spills.
 template <typename T, int D, int NT>
-__global__ void __launch_bounds__(NT) swa_decode_kernel(DecodeArgs a)
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(Elem<T>::kBytes == 1 ? 4 : 5)))
+swa_decode_kernel(DecodeArgs a)
 {
     constexpr int EPV = Elem<T>::kPerVec;   // elements per 16-byte vector
     constexpr int LPR = D / EPV;            // lanes per row
@@ -998,7 +1001,7 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     const int rowb = cache_row_bytes(p);
     const size_t lds_bytes = (size_t)a.lds_slots * (a.fuse_compaction ? (a.unordered ? 20 : 16) : 8) +
                              (size_t)a.stash_rows * rowb * 2;
-    const int nt = decode_block_threads(pairs, bound);
+    const int nt = decode_block_threads(pairs, bound, (p.flags & SWA_KV_INT8) != 0);
 
     auto launch = [&](const DecodeArgs& args) -> int {
         if (p.flags & SWA_KV_INT8) {

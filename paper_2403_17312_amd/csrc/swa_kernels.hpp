@@ -12,9 +12,9 @@ namespace swa {
 // Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.
 int ensure_dynamic_lds(const void* kernel, size_t bytes);
 
-// Threads per workgroup of the decode kernel for this many (sequence, head) pairs and
-// this bound on the cached length.
-int decode_block_threads(int64_t pairs, int len_bound);
+// Threads per workgroup of the decode kernel for this many (sequence, head) pairs, this bound on
+// the cached length and this cache format.
+int decode_block_threads(int64_t pairs, int len_bound, bool kv_int8);
 
 // Byte offset, inside the caller's workspace, of the slabs the head-shared step passes from its
 // first launch to its second (present only when SWA_HEAD_SHARED is set).
