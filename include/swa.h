@@ -112,9 +112,9 @@ typedef struct {
  * sum is reduced along the head dimension before the selection (the note in Algorithm 1's header):
  * the globally dynamic tokens of sequence s are the top-k of sum_hd score[s, hd, i], and all heads
  * of the sequence keep the same token set.  score stays per head (each head accumulates its own
- * attention weights); the sum over the heads is taken in fp32, head 0 first.  The call enqueues two
- * kernels (stream, publish; then reduce, select, finish) and needs the larger workspace that
- * swa_workspace_bytes reports for these flags.
+ * attention weights); the sum over the heads is taken in fp32, head 0 first.  The call enqueues
+ * three kernels (stream and publish; sum over the heads; select and finish) and needs the larger
+ * workspace that swa_workspace_bytes reports for these flags.
  */
 #define SWA_HEAD_SHARED 4
 

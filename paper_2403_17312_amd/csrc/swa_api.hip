@@ -135,7 +135,8 @@ size_t swa_workspace_bytes(const swa_params* params)
     if (swa::validate(params) != SWA_OK) return 0;
     size_t bytes = swa::shared_workspace_offset(*params);
     if (params->flags & SWA_HEAD_SHARED)
-        bytes += sizeof(float) * ((size_t)params->b * params->h * params->cap * 2 + (size_t)params->b * params->h * params->d);
+        bytes += sizeof(float) * ((size_t)params->b * params->h * params->cap * 2 + (size_t)params->b * params->h * params->d +
+                                  (size_t)params->b * params->cap);
     return (bytes + 255) & ~(size_t)255;
 }
 

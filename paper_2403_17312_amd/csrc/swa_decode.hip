@@ -51,13 +51,15 @@ struct DecodeArgs {
     float scale;
     int32_t fuse_compaction;
     int32_t unordered;    // fused compaction fills holes instead of shifting rows (order by pos only)
-    // Head-shared selection runs as two launches: phase 1 streams the cache and publishes the new
-    // importance, the attention weights and the dense output of every pair; phase 2 sums the
-    // importance over the heads of the sequence, selects once, and finishes output and compaction.
+    // Head-shared selection runs as three launches: phase 1 streams the cache and publishes the
+    // new importance, the attention weights and the dense output of every pair; a small kernel
+    // sums the new importance over the heads of every sequence; phase 2 selects from that sum
+    // (every head of a sequence reaches the same decision) and finishes output and compaction.
     int32_t phase;        // 0 = whole step in one launch
     float* ws_p;          // [b,h,cap] attention weights of phase 1
-    float* ws_snew;       // [b,h,cap] new importance of phase 1 (read across heads in phase 2)
+    float* ws_snew;       // [b,h,cap] new importance of phase 1
     float* ws_abar;       // [b,h,d]   dense attention output of phase 1
+    float* ws_tot;        // [b,cap]   new importance summed over the heads
     int32_t stash_rows;   // fused compaction: newest rows kept in LDS during the streaming pass
     // Compressed cache (Section V-B): per (pair, channel) scale and zero point of keys and values,
     // four fp32 arrays of qstride = b*h*d values each (lambda_K, z_K, lambda_V, z_V).
@@ -484,15 +486,13 @@ swa_decode_kernel(DecodeArgs a)
             if (tid == 0) s_ecnt = 0;
             const float* Pw = a.ws_p + pair * (int64_t)cap;
             const float* Sn = a.ws_snew + pair * (int64_t)cap;
-            const float* Sh = a.ws_snew + (int64_t)s * a.h * cap;     // head 0 of this sequence
+            const float* Tot = a.ws_tot + (int64_t)s * cap;
             for (int i = tid; i < m; i += NT) {
                 s_p[i] = Pw[i];
                 s_sc[i] = Sn[i];
                 const int posi = (i < len) ? Pp[i] : (n - 1);
                 s_pos[i] = posi;
-                float tot = 0.f;                                       // fixed order: head 0, 1, ...
-                for (int hh = 0; hh < a.h; ++hh) tot += Sh[(int64_t)hh * cap + i];
-                const uint32_t key = order_key(tot);
+                const uint32_t key = order_key(Tot[i]);
                 s_key[i] = key;
                 if (posi < wlo) {
                     const unsigned long long c = ((unsigned long long)key << 32) | (uint32_t)(~(uint32_t)posi);
@@ -933,6 +933,31 @@ swa_decode_kernel(DecodeArgs a)
     }
 }
 
+// Local attention sum reduced along the head dimension (the note in Algorithm 1's header):
+// tot[s, i] = sum over the heads of the new importance, fp32, head 0 first.
+constexpr int kHeadSumThreads = 64;
+__global__ void __launch_bounds__(kHeadSumThreads) swa_headsum_kernel(const float* snew, const int32_t* cache_len,
+                                                                      float* tot, int h, int cap)
+{
+    const int s = blockIdx.y;
+    const int i = blockIdx.x * kHeadSumThreads + threadIdx.x;
+    const int m = cache_len[s] + 1;
+    if (i >= m || i >= cap) return;
+    const float* Sh = snew + (int64_t)s * h * cap + i;
+    float t = 0.f;
+    // eight loads in flight, added in head order
+    int hh = 0;
+    for (; hh + 8 <= h; hh += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = Sh[(int64_t)(hh + k) * cap];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) t += v[k];
+    }
+    for (; hh < h; ++hh) t += Sh[(int64_t)hh * cap];
+    tot[(int64_t)s * cap + i] = t;
+}
+
 template <typename T, int D, int NT>
 static int launch_decode_nt(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, hipStream_t stream)
 {
@@ -987,13 +1012,14 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.unordered = (a.fuse_compaction && (p.flags & SWA_UNORDERED)) ? 1 : 0;
     const bool shared = a.unordered && (p.flags & SWA_HEAD_SHARED);
     a.phase = 0;
-    a.ws_p = a.ws_snew = a.ws_abar = nullptr;
+    a.ws_p = a.ws_snew = a.ws_abar = a.ws_tot = nullptr;
     if (shared) {
         char* base = static_cast<char*>(workspace) + shared_workspace_offset(p);
         const size_t slab = (size_t)p.b * p.h * p.cap * sizeof(float);
         a.ws_p = reinterpret_cast<float*>(base);
         a.ws_snew = reinterpret_cast<float*>(base + slab);
         a.ws_abar = reinterpret_cast<float*>(base + 2 * slab);
+        a.ws_tot = reinterpret_cast<float*>(base + 2 * slab + (size_t)p.b * p.h * p.d * sizeof(float));
     }
     a.stash_rows = (a.fuse_compaction && !a.unordered) ? decode_stash_rows(p) : 0;
 
@@ -1021,6 +1047,10 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.phase = 1;
     int rc = launch(a);
     if (rc != SWA_OK) return rc;
+    hipLaunchKernelGGL(swa_headsum_kernel, dim3((unsigned)((bound + kHeadSumThreads - 1) / kHeadSumThreads), (unsigned)p.b),
+                       dim3(kHeadSumThreads), 0, stream,
+                       a.ws_snew, a.cache_len, a.ws_tot, (int)p.h, (int)p.cap);
+    if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
     a.phase = 2;
     return launch(a);
 }

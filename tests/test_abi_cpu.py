@@ -77,7 +77,7 @@ def test_workspace_bytes(B):
     assert n >= 64 + 4 * 16 and n % 256 == 0
     assert B.swa_workspace_bytes(B.make_params(16, 32, 96, 545, 16, 8000, B.SWA_F16)) == 0
     ps = B.make_params(16, 32, 128, 576, 16, 8000, B.SWA_F16, flags=7)
-    assert B.swa_workspace_bytes(ps) >= n + 4 * (2 * 16 * 32 * 576 + 16 * 32 * 128)
+    assert B.swa_workspace_bytes(ps) >= n + 4 * (2 * 16 * 32 * 576 + 16 * 32 * 128 + 16 * 576)
 
 
 @pytest.mark.parametrize("kw,code", [
