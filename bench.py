@@ -32,8 +32,10 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
 
 
-def simulate_lengths(B, wl, lens):
-    """Host-side replay of the budget: per step, cached length m and kept count per sequence."""
+def simulate_lengths(B, wl, lens, compact_every=1):
+    """Host-side replay of the budget: per step, cached length m and kept count per sequence.
+    The cache shrinks to the kept set only on the steps that compact (every step by default;
+    0 = never)."""
     cur = list(lens)
     ms, keeps = [], []
     for t in range(wl.steps):
@@ -44,7 +46,7 @@ def simulate_lengths(B, wl, lens):
             keep, _, _ = B.swa_budget(n, m, wl.w, wl.sparsity_bp)
             m_t.append(m)
             k_t.append(keep)
-            cur[s] = keep
+            cur[s] = keep if (compact_every > 0 and (t + 1) % compact_every == 0) else m
         ms.append(m_t)
         keeps.append(k_t)
     return ms, keeps
@@ -53,7 +55,8 @@ def simulate_lengths(B, wl, lens):
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
-    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused, kv_int8=False):
+    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused, kv_int8=False, compact_every=1):
+        self.compact_every = compact_every
         self.fused = bool(fused)
         flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
                  "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED,
@@ -102,7 +105,7 @@ class Replica:
 
     def compact(self, B, t):
         st = self.st
-        if not self.fused:
+        if not self.fused and self.compact_every > 0 and (t + 1) % self.compact_every == 0:
             B.swa_compact_kv(self.params[t], st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt,
                              st.cache_len, st.workspace)
 
@@ -111,7 +114,8 @@ class Replica:
         self.compact(B, t)
 
 
-def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True, kv_int8=False):
+def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True, kv_int8=False,
+                   compact_every=1):
     dev = "cuda"
     T = wl.steps
     R = max(1, math.ceil(steps / T))
@@ -120,11 +124,11 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     lens = prompt["lengths"]
     inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(T)]
     q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R) if wl.prefill_R > 0 else None
-    ms, keeps = simulate_lengths(B, wl, lens)
+    ms, keeps = simulate_lengths(B, wl, lens, compact_every)
     len_bounds = [max(m_t) for m_t in ms]
 
     def fresh(n):
-        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8) for _ in range(n)]
+        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8, compact_every) for _ in range(n)]
         for r in reps:
             r.finish_prompt(q_tail)
         return reps
@@ -334,6 +338,9 @@ def main():
     ap.add_argument("--kv-int8", action="store_true",
                     help="compress the cache to 8-bit channel-wise codes after the prompt (swa_quantize_kv) "
                          "and step with swa_decode_step_q8 (fp16 workloads)")
+    ap.add_argument("--compact-every", type=int, default=1,
+                    help="with --step-mode split: call swa_compact_kv only every C-th step (0 = never); between "
+                         "compactions the cache keeps every token and the selection runs over all of them")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -357,7 +364,11 @@ def main():
     steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
     warmup = args.warmup if args.warmup is not None else wl.steps
     fused = args.step_mode if args.step_mode != "split" else False
-    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8)
+    if args.compact_every != 1 and args.step_mode != "split":
+        print("bench.py: --compact-every needs --step-mode split (the fused forms compact every step)", file=sys.stderr)
+        sys.exit(2)
+    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8,
+                         compact_every=args.compact_every)
 
     # Average launch duration of the dominant kernel.  Fused mode: the step IS one kernel, so the
     # HIP-event time of the graph replay divided by the number of launches is that kernel's
@@ -376,7 +387,7 @@ def main():
         "dtype": wl.dtype + ("+u8kv" if args.kv_int8 else ""), "data": "synthetic",
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
-                   "replicas": res["replicas"], "launch": args.mode,
+                   "replicas": res["replicas"], "launch": args.mode, "compact_every": args.compact_every,
                    "step": {"unordered": "swa_decode_step with SWA_FUSE_COMPACTION|SWA_UNORDERED (one kernel, "
                                          "hole-filling compaction, kept_idx not requested)",
                             "fused": "swa_decode_step with SWA_FUSE_COMPACTION (one kernel, token-ordered "
@@ -407,7 +418,8 @@ def main():
         k = o.steps * max(1, 256 // o.steps)
         if args.kv_int8 and o.dtype != "f16":
             continue
-        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8)
+        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8,
+                           compact_every=args.compact_every)
         a = r["alg_bytes_per_step"] / ((r["ms_per_step"] if fused else r["decode_kernel_ms_avg"]) * 1e-3) / 1e9
         others.append({"workload": name, "steps": k, "kv_tokens_per_s": r["kv_tokens_per_s"],
                        "ms_per_step": r["ms_per_step"], "decode_kernel_ms_avg": r["decode_kernel_ms_avg"],

@@ -52,6 +52,21 @@ def test_c1_tiny_without_compaction(env):
     assert rep.steps == 16
 
 
+def test_lazy_compaction_at_full_size(env):
+    # the cache keeps every token between compactions and the selection runs over all of them:
+    # config 2 compacting every 8th step (every pair), config 3 never compacting (sampled pairs)
+    O, B, W, LS = env
+    _say("c2 lockstep, compaction every 8 steps")
+    rep = LS.run_lockstep(W.CONFIGS["c2_opt6p7b"], compact_every=8, use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32 and rep.evictions > 0
+    _say("c3 lockstep, never compacted, sampled pairs")
+    rep = LS.run_lockstep(W.CONFIGS["c3_opt13b"], compact_every=0, steps=12, seqs=[0, 31, 63],
+                          heads=[0, 17, 39], use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 12
+
+
 def test_c2_opt6p7b_every_pair_every_step(env):
     O, B, W, LS = env
     _say("c2 lockstep")
