@@ -37,7 +37,9 @@
  *     the special case w = nearest-integer(n*r/2);
  *   - the importance score is a running sum of attention-weight rows: seeded
  *     with the sum of the last R prompt rows (Alg. 1 line 2) and increased by
- *     the current row at every decode step;
+ *     the current row at every decode step; the *_window routines instead keep
+ *     the last R rows and sum exactly those, which is Alg. 1 line 2 to the
+ *     letter (with the current row counted, as everywhere here);
  *   - global candidates exclude the local window, selection is per
  *     (sequence, head) -- or, on request, per sequence from the local
  *     attention sum reduced over the heads, as Algorithm 1's header notes --
@@ -464,6 +466,116 @@ int swa_oracle_prefill_scores(int32_t b, int32_t h, int32_t d, int32_t cap, int3
         free(aw);
     }
     return failed ? SWA_ORACLE_ERR_ALLOC : SWA_ORACLE_OK;
+}
+
+
+/* ------------------------------------------------------------------------ */
+/* Strict local attention sum (Alg. 1 line 2 taken literally): S is the sum  */
+/* of the R most recent rows of the attention-weight matrix and nothing      */
+/* older.  The rows are kept per pair in ring [b, h, R, cap]: ring row j     */
+/* holds, slot by slot, the weights that one of the last R queries gave to   */
+/* the tokens now cached (0 where the token did not exist yet).  A step      */
+/* overwrites ring row `row` (the caller advances it modulo R, so the oldest */
+/* row goes first).                                                          */
+/* ------------------------------------------------------------------------ */
+
+/* The last R rows of the prompt's causal attention-weight matrix, one per   */
+/* ring row: ring row r is the query at position t = s - R + r over keys     */
+/* 0..t; rows with t < 0 and entries beyond t are 0.                         */
+int swa_oracle_prefill_rows(int32_t b, int32_t h, int32_t d, int32_t cap, int32_t R,
+                            double scale, const double *q_tail, const double *K,
+                            const int32_t *cache_len, double *ring)
+{
+    int64_t pairs = (int64_t)b * h;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t pair = 0; pair < pairs; ++pair) {
+        int32_t s = cache_len[pair / h];
+        for (int32_t r = 0; r < R; ++r) {
+            double *row = ring + (pair * R + r) * (int64_t)cap;
+            for (int32_t j = 0; j < cap; ++j) row[j] = 0.0;
+            int32_t t = s - R + r;
+            if (t < 0) continue;
+            const double *qr = q_tail + (pair * R + r) * d;
+            double zmax = -INFINITY;
+            for (int32_t j = 0; j <= t; ++j) {
+                double z = 0.0;
+                for (int32_t c = 0; c < d; ++c) z += qr[c] * K[(pair * cap + j) * d + c];
+                row[j] = z * scale;
+                if (row[j] > zmax) zmax = row[j];
+            }
+            double denom = 0.0;
+            for (int32_t j = 0; j <= t; ++j) {
+                row[j] = exp(row[j] - zmax);
+                denom += row[j];
+            }
+            for (int32_t j = 0; j <= t; ++j) row[j] /= denom;
+        }
+    }
+    return SWA_ORACLE_OK;
+}
+
+/* The current row replaces ring row `row`; score = sum of the R ring rows.  */
+/* The token appended in this step (slot m-1) has no earlier rows.           */
+void swa_oracle_window_accumulate(int32_t b, int32_t h, int32_t cap, int32_t R, int32_t row,
+                                  const double *probs, const int32_t *cache_len, double *ring,
+                                  double *score)
+{
+    int64_t pairs = (int64_t)b * h;
+#pragma omp parallel for schedule(static)
+    for (int64_t pair = 0; pair < pairs; ++pair) {
+        int32_t m = cache_len[pair / h];
+        double *Rg = ring + pair * (int64_t)R * cap;
+        for (int32_t j = 0; j < R; ++j) Rg[(int64_t)j * cap + (m - 1)] = 0.0;
+        for (int32_t i = 0; i < m; ++i) Rg[(int64_t)row * cap + i] = probs[pair * cap + i];
+        for (int32_t i = 0; i < m; ++i) {
+            double t = 0.0;
+            for (int32_t j = 0; j < R; ++j) t += Rg[(int64_t)j * cap + i];
+            score[pair * cap + i] = t;
+        }
+    }
+}
+
+/* The ring's columns follow their tokens through a compaction. */
+int swa_oracle_compact_ring(int32_t b, int32_t h, int32_t cap, int32_t R, double *ring,
+                            const int32_t *kept_idx, const int32_t *kept_cnt)
+{
+    int64_t pairs = (int64_t)b * h;
+    int failed = 0;
+#pragma omp parallel for schedule(static) reduction(| : failed)
+    for (int64_t pair = 0; pair < pairs; ++pair) {
+        int32_t cnt = kept_cnt[pair / h];
+        double *tmp = (double *)malloc(sizeof(double) * (size_t)(cnt > 0 ? cnt : 1));
+        if (!tmp) {
+            failed = 1;
+            continue;
+        }
+        for (int32_t j = 0; j < R; ++j) {
+            double *row = ring + (pair * R + j) * (int64_t)cap;
+            for (int32_t k = 0; k < cnt; ++k) tmp[k] = row[kept_idx[pair * cap + k]];
+            for (int32_t k = 0; k < cnt; ++k) row[k] = tmp[k];
+            for (int32_t k = cnt; k < cap; ++k) row[k] = 0.0;
+        }
+        free(tmp);
+    }
+    return failed ? SWA_ORACLE_ERR_ALLOC : SWA_ORACLE_OK;
+}
+
+/* One decode step with the strict local attention sum: as swa_oracle_decode_step, with the    */
+/* importance taken from the ring instead of the running sum.                                  */
+int swa_oracle_decode_step_window(int32_t b, int32_t h, int32_t d, int32_t cap, int32_t w,
+                                  int32_t sparsity_bp, double scale, int32_t R, int32_t row,
+                                  const double *q, const double *k_new, const double *v_new,
+                                  double *K, double *V, double *ring, double *score, int32_t *pos,
+                                  int32_t *cache_len, const int32_t *seq_len,
+                                  int32_t *kept_idx, int32_t *kept_cnt, double *out, double *probs)
+{
+    int rc = swa_oracle_append(b, h, d, cap, k_new, v_new, K, V, score, pos, cache_len, seq_len);
+    if (rc) return rc;
+    swa_oracle_probs(b, h, d, cap, scale, q, K, cache_len, probs);
+    swa_oracle_window_accumulate(b, h, cap, R, row, probs, cache_len, ring, score);
+    rc = swa_oracle_select(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt);
+    if (rc) return rc;
+    return swa_oracle_sparse_attention(b, h, d, cap, scale, q, K, V, kept_idx, kept_cnt, out);
 }
 
 

@@ -220,3 +220,45 @@ def kv_dequantize(codes, count, lam, zero):
                                    _pf(np.ascontiguousarray(lam, dtype=np.float32)),
                                    _pf(np.ascontiguousarray(zero, dtype=np.float32)), _pd(X))
     return X
+
+
+def prefill_rows(q_tail, K, cache_len, scale: float):
+    """q_tail [b,h,R,d] -> ring [b,h,R,cap]: the last R rows of the prompt's causal attention weights."""
+    b, h, d, cap = _dims(K)
+    q_tail = _f64(q_tail)
+    R = q_tail.shape[2]
+    ring = np.zeros((K.shape[0], K.shape[1], R, K.shape[2]), dtype=np.float64)
+    rc = lib().swa_oracle_prefill_rows(b, h, d, cap, ctypes.c_int32(R), ctypes.c_double(scale),
+                                       _pd(q_tail), _pd(K), _pi(_i32(cache_len)), _pd(ring))
+    _check(rc, "prefill_rows")
+    return ring
+
+
+def compact_ring(ring, kept_idx, kept_cnt) -> None:
+    """In place: the ring's columns follow the kept tokens."""
+    b, h, R, cap = ring.shape
+    rc = lib().swa_oracle_compact_ring(ctypes.c_int32(b), ctypes.c_int32(h), ctypes.c_int32(cap),
+                                       ctypes.c_int32(R), _pd(ring), _pi(_i32(kept_idx)),
+                                       _pi(_i32(kept_cnt)))
+    _check(rc, "compact_ring")
+
+
+def decode_step_window(q, k_new, v_new, K, V, ring, row: int, score, pos, cache_len, seq_len, w: int,
+                       sparsity_bp: int, scale: float):
+    """One step with the strict local attention sum.  In place: K, V, ring, score, pos, cache_len.
+
+    Returns (kept_idx, kept_cnt, out, probs).
+    """
+    b, h, d, cap = _dims(K)
+    R = ring.shape[2]
+    kept_idx = np.full(K.shape[:3], -1, dtype=np.int32)
+    kept_cnt = np.zeros((K.shape[0],), dtype=np.int32)
+    out = np.zeros((K.shape[0], K.shape[1], K.shape[3]), dtype=np.float64)
+    p = np.zeros(K.shape[:3], dtype=np.float64)
+    rc = lib().swa_oracle_decode_step_window(
+        b, h, d, cap, ctypes.c_int32(w), ctypes.c_int32(sparsity_bp), ctypes.c_double(scale),
+        ctypes.c_int32(R), ctypes.c_int32(row), _pd(_f64(q)), _pd(_f64(k_new)), _pd(_f64(v_new)),
+        _pd(K), _pd(V), _pd(ring), _pd(score), _pi(pos), _pi(cache_len), _pi(_i32(seq_len)),
+        _pi(kept_idx), _pi(kept_cnt), _pd(out), _pd(p))
+    _check(rc, "decode_step_window")
+    return kept_idx, kept_cnt, out, p
