@@ -52,6 +52,11 @@ def simulate_lengths(B, wl, lens, compact_every=1):
     return ms, keeps
 
 
+def torch_zeros(shape, device):
+    import torch
+    return torch.zeros(shape, dtype=torch.float32, device=device)
+
+
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
@@ -60,7 +65,10 @@ class Replica:
         self.fused = bool(fused)
         flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
                  "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED,
-                 "shared": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED}[fused]
+                 "shared": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED,
+                 "window": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED}[fused]
+        self.window_rows = min(max(wl.w, 1), B.SWA_MAX_WINDOW_ROWS) if fused == "window" else 0
+        self.ring = None
         self.fused = flags != 0
         params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, flags=flags)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
@@ -73,13 +81,20 @@ class Replica:
         self.seq_lens = torch.stack([base + (t + 1) for t in range(wl.steps)]).contiguous()  # [T, b]
         # per-step params: the host knows an upper bound on the cached length of every step
         self.kv_int8 = kv_int8
+        self.B = B
         qf = B.SWA_KV_INT8 if kv_int8 else 0
         self.params = [B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype,
                                      len_bound=lb, flags=flags | qf) for lb in len_bounds]
 
     def finish_prompt(self, q_tail):
         """End of the prompt: importance seed (if the workload has one), then KV compression."""
-        if q_tail is not None:
+        if self.window_rows:
+            st, R = self.st, self.window_rows
+            self.ring = torch_zeros((st.K.shape[0], st.K.shape[1], R, st.K.shape[2]), st.K.device)
+            if q_tail is not None:
+                self.B.swa_prefill_rows(st.params, q_tail[:, :, -R:].contiguous(), R, st.K, st.cache_len, self.ring,
+                                        st.workspace)
+        elif q_tail is not None:
             self.st.prefill_scores(q_tail)
         if self.kv_int8:
             self.st.quantize()
@@ -95,7 +110,11 @@ class Replica:
 
     def _call(self, B, t, q, kn, vn, kept_idx):
         st = self.st
-        if self.kv_int8:
+        if self.window_rows:
+            B.swa_decode_step_window(self.params[t], q, kn, vn, st.K, st.V, self.ring, self.window_rows,
+                                     t % self.window_rows, st.score, st.pos, st.cache_len, self.seq_lens[t],
+                                     kept_idx, st.kept_cnt, st.out, None, st.workspace)
+        elif self.kv_int8:
             B.swa_decode_step_q8(self.params[t], q, kn, vn, st.K, st.V, st.qparams, st.score, st.pos,
                                  st.cache_len, self.seq_lens[t], kept_idx, st.kept_cnt, st.out, None,
                                  st.workspace)
@@ -133,8 +152,10 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
             r.finish_prompt(q_tail)
         return reps
 
+    window_rows = min(max(wl.w, 1), B.SWA_MAX_WINDOW_ROWS) if fused == "window" else 0
+
     def abp(m, k):
-        return W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k, kv_int8)
+        return W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k, kv_int8, window_rows)
 
     def run(reps, count):
         n = len(reps)
@@ -330,10 +351,12 @@ def main():
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default="c2_opt6p7b")
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
-    ap.add_argument("--step-mode", choices=["unordered", "fused", "split", "shared"], default="unordered",
+    ap.add_argument("--step-mode", choices=["unordered", "fused", "split", "shared", "window"], default="unordered",
                     help="fused: one kernel per step, cache kept in token order; unordered: one kernel per "
                          "step, compaction fills holes (SWA_UNORDERED); shared: unordered with one token set per "
-                         "sequence from the head-summed importance (SWA_HEAD_SHARED, two launches); "
+                         "sequence from the head-summed importance (SWA_HEAD_SHARED); window: unordered with "
+                         "the strict local attention sum over a ring of w attention rows "
+                         "(swa_decode_step_window); "
                          "split: swa_decode_step + swa_compact_kv")
     ap.add_argument("--kv-int8", action="store_true",
                     help="compress the cache to 8-bit channel-wise codes after the prompt (swa_quantize_kv) "
@@ -394,6 +417,8 @@ def main():
                                      "compaction, kept_idx not requested)",
                             "shared": "swa_decode_step with SWA_HEAD_SHARED (two launches around the "
                                       "head-summed importance, hole-filling compaction)",
+                            "window": "swa_decode_step_window (strict local attention sum over min(w, 64) rows, "
+                                      "hole-filling compaction)",
                             "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]},
         "roofline": {
             "bound": "hbm", "kernel": "swa_decode_kernel",

@@ -240,6 +240,41 @@ int swa_decode_step_q8(const swa_params *params, const void *q, const void *k_ne
                        int32_t *kept_idx, int32_t *kept_cnt, void *out, float *probs_dbg,
                        void *workspace, void *stream);
 
+/*
+ * Strict local attention sum: Algorithm 1 line 2 to the letter.  The importance of a cached
+ * token is the sum of the attention weights it received from the R most recent queries and from
+ * no older one (swa_decode_step keeps a running sum instead).  The rows are kept per pair in
+ *   ring [b,h,R,cap] float32: ring[s,hd,j,i] = weight that the query of ring row j gave to the
+ *   token now in slot i (0 where the token did not exist yet, or for a row not written yet).
+ */
+#define SWA_MAX_WINDOW_ROWS 64
+
+/*
+ * The ring at the end of the prompt: ring row r = attention weights of the prompt query at
+ * position t = cache_len - R + r over keys 0..t (Eq. 1 with the causal mask); rows with t < 0 and
+ * entries beyond t or beyond cache_len are 0.  Their sum over r is what swa_prefill_scores gives.
+ * Decode step number k (0-based) after this call should replace ring row k mod R (oldest first).
+ *   q_tail [b,h,R,d] dtype (in), 1 <= R <= SWA_MAX_WINDOW_ROWS; k_cache, cache_len (in); ring (out).
+ */
+int swa_prefill_rows(const swa_params *params, const void *q_tail, int32_t R, const void *k_cache,
+                     const int32_t *cache_len, float *ring, void *workspace, void *stream);
+
+/*
+ * swa_decode_step with the strict local attention sum.  params->flags must be exactly
+ * SWA_FUSE_COMPACTION | SWA_UNORDERED.  Differences from swa_decode_step in that form:
+ *   3'. importance: ring row `ring_row` (0 <= ring_row < R) is replaced by this step's weights p,
+ *       and score[i] = sum over the R ring rows at slot i, added in row order in fp32; the token
+ *       appended in this step has no earlier rows.  score is output only (the old content is
+ *       not read); selection, output and compaction then proceed as usual, and the ring's
+ *       columns move with their tokens, so ring stays aligned with the compacted cache.
+ * ring [b,h,R,cap] (in/out).  The caller advances ring_row by one modulo R per step.
+ */
+int swa_decode_step_window(const swa_params *params, const void *q, const void *k_new,
+                           const void *v_new, void *k_cache, void *v_cache, float *ring, int32_t R,
+                           int32_t ring_row, float *score, int32_t *pos, int32_t *cache_len,
+                           const int32_t *seq_len, int32_t *kept_idx, int32_t *kept_cnt, void *out,
+                           float *probs_dbg, void *workspace, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -29,11 +29,12 @@ SWA_UNORDERED = 2
 SWA_HEAD_SHARED = 4
 SWA_MAX_UNORDERED_SLOTS = 7168
 SWA_KV_INT8 = 8
+SWA_MAX_WINDOW_ROWS = 64
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
-           "swa_decode_step_q8"]
+           "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window"]
 
 
 class SwaParams(ctypes.Structure):
@@ -83,6 +84,10 @@ def lib():
         L.swa_quantize_kv.argtypes = [pp] + [vp] * 7
         L.swa_decode_step_q8.restype = ctypes.c_int
         L.swa_decode_step_q8.argtypes = [pp] + [vp] * 16
+        L.swa_prefill_rows.restype = ctypes.c_int
+        L.swa_prefill_rows.argtypes = [pp, vp, ctypes.c_int32, vp, i32p, vp, vp, vp]
+        L.swa_decode_step_window.restype = ctypes.c_int
+        L.swa_decode_step_window.argtypes = [pp] + [vp] * 6 + [ctypes.c_int32] * 2 + [vp] * 10
         _lib = L
     return _lib
 
@@ -170,6 +175,24 @@ def swa_decode_step_q8(params: SwaParams, q, k_new, v_new, k_codes, v_codes, qpa
                                     _ptr(pos), _ptr(cache_len), _ptr(seq_len), _ptr(kept_idx),
                                     _ptr(kept_cnt), _ptr(out), _ptr(probs_dbg), _ptr(workspace),
                                     _stream(stream)), "swa_decode_step_q8")
+
+
+def swa_prefill_rows(params: SwaParams, q_tail, R: int, k_cache, cache_len, ring, workspace,
+                     stream=None) -> None:
+    _check(lib().swa_prefill_rows(ctypes.byref(params), _ptr(q_tail), int(R), _ptr(k_cache),
+                                  _ptr(cache_len), _ptr(ring), _ptr(workspace), _stream(stream)),
+           "swa_prefill_rows")
+
+
+def swa_decode_step_window(params: SwaParams, q, k_new, v_new, k_cache, v_cache, ring, R: int,
+                           ring_row: int, score, pos, cache_len, seq_len, kept_idx, kept_cnt, out,
+                           probs_dbg, workspace, stream=None) -> None:
+    _check(lib().swa_decode_step_window(ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                        _ptr(k_cache), _ptr(v_cache), _ptr(ring), int(R),
+                                        int(ring_row), _ptr(score), _ptr(pos), _ptr(cache_len),
+                                        _ptr(seq_len), _ptr(kept_idx), _ptr(kept_cnt), _ptr(out),
+                                        _ptr(probs_dbg), _ptr(workspace), _stream(stream)),
+           "swa_decode_step_window")
 
 
 def swa_compact_kv(params: SwaParams, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,

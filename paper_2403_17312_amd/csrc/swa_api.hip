@@ -187,14 +187,29 @@ int swa_prefill_scores(const swa_params* params, const void* q_tail, int32_t R, 
     if (!q_tail || !k_cache || !cache_len || !score) return SWA_ERR_NULL;
     if (R < 1 || R > SWA_MAX_PREFILL_ROWS) return SWA_ERR_BAD_SHAPE;
     if (!swa::aligned16(q_tail) || !swa::aligned16(k_cache)) return SWA_ERR_ALIGNMENT;
-    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, score,
+    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, score, nullptr,
+                               static_cast<hipStream_t>(stream));
+}
+
+int swa_prefill_rows(const swa_params* params, const void* q_tail, int32_t R, const void* k_cache,
+                     const int32_t* cache_len, float* ring, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    (void)workspace;
+    if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (!q_tail || !k_cache || !cache_len || !ring) return SWA_ERR_NULL;
+    if (R < 1 || R > SWA_MAX_WINDOW_ROWS) return SWA_ERR_BAD_SHAPE;
+    if (!swa::aligned16(q_tail) || !swa::aligned16(k_cache)) return SWA_ERR_ALIGNMENT;
+    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, nullptr, ring,
                                static_cast<hipStream_t>(stream));
 }
 
 static int decode_common(const swa_params* params, const void* q, const void* k_new, const void* v_new,
                          void* k_cache, void* v_cache, const float* qparams, float* score, int32_t* pos,
                          int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt,
-                         void* out, float* probs_dbg, void* workspace, void* stream)
+                         void* out, float* probs_dbg, void* workspace, void* stream, float* ring = nullptr,
+                         int32_t ring_rows = 0, int32_t ring_row = 0)
 {
     const bool fuse = (params->flags & SWA_FUSE_COMPACTION) != 0;
     if (!q || !k_new || !v_new || !k_cache || !v_cache || !score || !pos || !cache_len || !seq_len ||
@@ -209,8 +224,22 @@ static int decode_common(const swa_params* params, const void* q, const void* k_
         !swa::aligned16(v_cache) || !swa::aligned16(out))
         return SWA_ERR_ALIGNMENT;
     return swa::launch_decode(*params, swa::effective_scale(params), q, k_new, v_new, k_cache, v_cache, score,
-                              pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, qparams,
-                              static_cast<hipStream_t>(stream));
+                              pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, qparams, ring,
+                              ring_rows, ring_row, static_cast<hipStream_t>(stream));
+}
+
+int swa_decode_step_window(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, float* ring, int32_t R, int32_t ring_row, float* score,
+                           int32_t* pos, int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx,
+                           int32_t* kept_cnt, void* out, float* probs_dbg, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (params->flags != (SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
+    if (!ring) return SWA_ERR_NULL;
+    if (R < 1 || R > SWA_MAX_WINDOW_ROWS || ring_row < 0 || ring_row >= R) return SWA_ERR_BAD_SHAPE;
+    return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
+                         kept_idx, kept_cnt, out, probs_dbg, workspace, stream, ring, R, ring_row);
 }
 
 int swa_decode_step(const swa_params* params, const void* q, const void* k_new, const void* v_new,

@@ -65,6 +65,11 @@ struct DecodeArgs {
     // four fp32 arrays of qstride = b*h*d values each (lambda_K, z_K, lambda_V, z_V).
     const float* qparams;
     int64_t qstride;
+    // Strict local attention sum (Algorithm 1 line 2): the last ring_rows attention rows per pair,
+    // [b,h,ring_rows,cap]; this step overwrites row ring_row and the importance is the sum of
+    // the rows.  NULL: running sum in `score`.
+    float* ring;
+    int32_t ring_rows, ring_row;
 };
 
 constexpr int kMaxFix = 8;           // evicted rows the subtractive schedule handles
@@ -244,7 +249,7 @@ swa_decode_kernel(DecodeArgs a)
 #pragma unroll
         for (int k = 0; k < SPF; ++k) {
             const int i = tid + k * NT;
-            sold[k] = (i < len) ? Sp[i] : 0.f;
+            sold[k] = (i < len && !a.ring) ? Sp[i] : 0.f;
         }
         int32_t pold[SPF];
 #pragma unroll
@@ -401,6 +406,27 @@ swa_decode_kernel(DecodeArgs a)
 #pragma unroll
         for (int v = 0; v < NW; ++v) sum += s_redB[v];
 
+        // Strict window: the rows of the ring in index order, the current weight standing in for
+        // the row this step replaces; a token appended in this step has no earlier rows.
+        float* Rg = a.ring ? a.ring + pair * (int64_t)a.ring_rows * cap : nullptr;
+        auto window_sum = [&](int i, float p) -> float {
+            float t = 0.f;
+            const bool old = i < len;
+            int j = 0;
+            for (; j + 8 <= a.ring_rows; j += 8) {
+                float v[8];
+#pragma unroll
+                for (int k = 0; k < 8; ++k) v[k] = (old && j + k != a.ring_row) ? Rg[(int64_t)(j + k) * cap + i] : 0.f;
+#pragma unroll
+                for (int k = 0; k < 8; ++k) t += (j + k == a.ring_row) ? p : v[k];
+            }
+            for (; j < a.ring_rows; ++j) {
+                const float v = (old && j != a.ring_row) ? Rg[(int64_t)j * cap + i] : 0.f;
+                t += (j == a.ring_row) ? p : v;
+            }
+            return t;
+        };
+
         // ---- importance accumulation; arg-min bookkeeping for the E == 1 case ------------
 #pragma unroll
         for (int k = 0; k < SPF; ++k) {
@@ -408,7 +434,7 @@ swa_decode_kernel(DecodeArgs a)
             if (i < m) {
                 const float p = s_p[i] / sum;
                 s_p[i] = p;
-                const float sc = sold[k] + p;
+                const float sc = a.ring ? window_sum(i, p) : sold[k] + p;
                 if (fc) {
                     s_sc[i] = sc;
                     s_pos[i] = pold[k];
@@ -434,8 +460,7 @@ swa_decode_kernel(DecodeArgs a)
         for (int i = tid + SPF * NT; i < m; i += NT) {
             const float p = s_p[i] / sum;
             s_p[i] = p;
-            const float old = (i == len) ? 0.f : Sp[i];
-            const float sc = old + p;
+            const float sc = a.ring ? window_sum(i, p) : ((i == len) ? 0.f : Sp[i]) + p;
             const int posi = (fc && i < len) ? Pp[i] : (n - 1);
             if (fc) {
                 s_sc[i] = sc;
@@ -824,6 +849,30 @@ swa_decode_kernel(DecodeArgs a)
                 src = src < 0 ? 0 : (src > len ? len : src);
                 Sp[j] = s_sc[src];
                 if (src != j || src == len) Pp[j] = s_pos[src];
+                if (a.ring) a.ring[(pair * a.ring_rows + a.ring_row) * (int64_t)cap + j] = s_p[src];
+            }
+            if (a.ring) {
+                // The other rows of the ring follow the tokens that change slot (sources at or above
+                // `keep`, destinations below it: disjoint); the new token's column is zero there.
+                float* Rn = a.ring + pair * (int64_t)a.ring_rows * cap;
+                const int Rr = a.ring_rows;
+                if (!have_list) {
+                    const int dst = (jstar < len) ? jstar : len;
+                    if (dst < keep)
+                        for (int j = tid; j < Rr; j += NT)
+                            if (j != a.ring_row) Rn[(int64_t)j * cap + dst] = 0.f;
+                } else {
+                    for (int e = tid; e < n_moves * Rr; e += NT) {
+                        const int k = e / Rr, j = e - k * Rr;
+                        int src = s_movers[k], dst = s_holes[k];
+                        src = src > len ? len : src;
+                        dst = dst >= keep ? keep - 1 : dst;
+                        if (j != a.ring_row) Rn[(int64_t)j * cap + dst] = (src == len) ? 0.f : Rn[(int64_t)j * cap + src];
+                    }
+                    if (len < keep)       // the new token stays in slot len: clear what the slot held before
+                        for (int j = tid; j < Rr; j += NT)
+                            if (j != a.ring_row) Rn[(int64_t)j * cap + len] = 0.f;
+                }
             }
             if (bag) {
                 // Sources (slots >= keep, or the new row) and destinations (holes < keep) are
@@ -981,9 +1030,13 @@ static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes,
 int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
                   void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
                   const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
-                  float* probs_dbg, void* workspace, const float* qparams, hipStream_t stream)
+                  float* probs_dbg, void* workspace, const float* qparams, float* ring, int32_t ring_rows,
+                  int32_t ring_row, hipStream_t stream)
 {
     DecodeArgs a;
+    a.ring = ring;
+    a.ring_rows = ring_rows;
+    a.ring_row = ring_row;
     a.qparams = qparams;
     a.qstride = (int64_t)p.b * p.h * p.d;
     a.q = static_cast<const char*>(q);

@@ -34,7 +34,8 @@ int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stre
 int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
                   void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
                   const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
-                  float* probs_dbg, void* workspace, const float* qparams, hipStream_t stream);
+                  float* probs_dbg, void* workspace, const float* qparams, float* ring, int32_t ring_rows,
+                  int32_t ring_row, hipStream_t stream);
 
 // Channel-wise 8-bit compression of an fp16 cache (Section V-B): parameters from the cached rows,
 // then the codes.  qparams: four fp32 arrays of b*h*d values (lambda_K, z_K, lambda_V, z_V).
@@ -46,6 +47,6 @@ int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* sco
                    hipStream_t stream);
 
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
-                   const int32_t* cache_len, float* score, hipStream_t stream);
+                   const int32_t* cache_len, float* score, float* rows, hipStream_t stream);
 
 }  // namespace swa

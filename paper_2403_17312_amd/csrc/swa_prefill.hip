@@ -23,7 +23,8 @@ struct PrefillArgs {
     const char* q_tail;
     const char* k_cache;
     const int32_t* cache_len;
-    float* score;
+    float* score;   // column sums over the R rows, or NULL
+    float* rows;    // [b,h,R,cap] the R rows themselves, or NULL
     int32_t h, cap, R;
     float scale_log2e;
 };
@@ -98,10 +99,14 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     const int R = a.R;
     int s = a.cache_len[pair / a.h];
     s = s > cap ? cap : s;
-    float* Sp = a.score + pair * (int64_t)cap;
+    float* Sp = a.score ? a.score + pair * (int64_t)cap : nullptr;
+    float* Rp = a.rows ? a.rows + pair * (int64_t)R * cap : nullptr;
 
     if (s <= 0) {
-        for (int j = tid; j < cap; j += NT) Sp[j] = 0.f;
+        if (Sp)
+            for (int j = tid; j < cap; j += NT) Sp[j] = 0.f;
+        if (Rp)
+            for (int j = tid; j < R * cap; j += NT) Rp[j] = 0.f;
         return;
     }
 
@@ -227,11 +232,12 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
                     const bool vis = (r < R) && (key <= t_off + r);
                     const float p = __builtin_amdgcn_exp2f(c[4 * g + j] * a.scale_log2e - Mr[j]) * Ir[j];
                     colsum += vis ? p : 0.f;
+                    if (Rp && r < R && key < s) Rp[(int64_t)r * cap + key] = vis ? p : 0.f;
                 }
             }
         }
         colsum += __shfl_xor(colsum, 32, kWave);
-        if (hb == 0 && key < s) Sp[key] = colsum;
+        if (Sp && hb == 0 && key < s) Sp[key] = colsum;
     };
     {
         Vec16 kA[NV], kB[NV];
@@ -243,7 +249,11 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
             if (tile + NW < ntiles) colsum_tile(tile + NW, kB);
         }
     }
-    for (int j = s + tid; j < cap; j += NT) Sp[j] = 0.f;
+    if (Sp)
+        for (int j = s + tid; j < cap; j += NT) Sp[j] = 0.f;
+    if (Rp)
+        for (int r = 0; r < R; ++r)
+            for (int j = s + tid; j < cap; j += NT) Rp[(int64_t)r * cap + j] = 0.f;
 }
 
 template <typename T, int D>
@@ -261,9 +271,10 @@ static int launch_prefill_t(const PrefillArgs& a, int64_t pairs, hipStream_t str
 }
 
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
-                   const int32_t* cache_len, float* score, hipStream_t stream)
+                   const int32_t* cache_len, float* score, float* rows, hipStream_t stream)
 {
     PrefillArgs a;
+    a.rows = rows;
     a.q_tail = static_cast<const char*>(q_tail);
     a.k_cache = static_cast<const char*>(k_cache);
     a.cache_len = cache_len;

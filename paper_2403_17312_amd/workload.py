@@ -178,7 +178,8 @@ def make_step(wl: Workload, t: int, mu: torch.Tensor):
     return q, k_new, v_new
 
 
-def algorithmic_bytes_per_pair(d: int, elem_bytes: int, m: int, keep: int, kv_int8: bool = False) -> int:
+def algorithmic_bytes_per_pair(d: int, elem_bytes: int, m: int, keep: int, kv_int8: bool = False,
+                               window_rows: int = 0) -> int:
     """Bytes one (sequence, head) pair must move in one decode step.
 
     m key rows + keep value rows + importance read and write over m slots + the
@@ -187,7 +188,13 @@ def algorithmic_bytes_per_pair(d: int, elem_bytes: int, m: int, keep: int, kv_in
     per-token figure of the paper's caching-time model (Section V-A).  With the
     8-bit compressed cache of Section V-B a cache row is d bytes, the per-step
     rows stay fp16, and the pair's four fp32 parameter rows are read as well.
+    With the strict local attention sum over a ring of window_rows attention rows,
+    the other window_rows - 1 rows are read over the m slots and this step's row
+    is written over the kept ones (in place of the running sum's read).
     """
+    if window_rows > 0:
+        row = d * elem_bytes
+        return row * m + row * keep + 4 * (window_rows - 1) * m + 4 * m + 4 * keep + 4 * row + 4 * keep
     if kv_int8:
         return d * m + d * keep + 8 * m + 4 * (2 * d) + 4 * (4 * d) + 4 * keep
     row = d * elem_bytes

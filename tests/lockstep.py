@@ -312,3 +312,156 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             print(f"  [{wl.name}] step {t}: m={len_o.tolist()[:4]} ok", flush=True)
     assert st.check_status() == 0
     return rep
+
+
+def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[int] = None,
+                        seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
+                        slack: str = "nan", use_len_bound: bool = False, seed_rows: bool = True,
+                        sparsity_of_step=None) -> Report:
+    """Lock-step parity of swa_decode_step_window (strict local attention sum over a ring of R rows,
+    unordered fused compaction) against the oracle's *_window routines.  The oracle's ring is the
+    GPU's fp32 ring in token order (adopted row by row), so after every compaction the two rings
+    must agree bit for bit; the importance is rebuilt from the GPU's own fp32 rows exactly as the
+    kernel adds them (row order, fp32) and the selection is checked on those values."""
+    steps = wl.steps if steps is None else steps
+    seqs = list(range(wl.b)) if seqs is None else list(seqs)
+    heads = list(range(wl.h)) if heads is None else list(heads)
+    prompt = W.make_prompt(wl, device, slack=slack)
+    st = new_state(wl, prompt)
+    st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+    rep = Report(pairs=len(seqs) * len(heads))
+    seqs_t = torch.tensor(seqs, device=device)
+    heads_t = torch.tensor(heads, device=device)
+    K_o = _np64(_sub(st.K, seqs_t, heads_t))
+    V_o = _np64(_sub(st.V, seqs_t, heads_t))
+    pos_o = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
+    len_o = st.cache_len[seqs_t].cpu().numpy().copy()
+    n_o = len_o.copy()
+    score_o = np.zeros(K_o.shape[:3])
+    ring = torch.zeros((wl.b, wl.h, R, wl.cap), dtype=torch.float32, device=device)
+    if seed_rows:
+        q_tail = W.make_q_tail(wl, prompt["mu"], R)
+        B.swa_prefill_rows(st.params, q_tail, R, st.K, st.cache_len, ring, st.workspace)
+        ring_ref = O.prefill_rows(_np64(_sub(q_tail, seqs_t, heads_t)), K_o, len_o, wl.scale)
+        ring_g = _np64(_sub(ring, seqs_t, heads_t))
+        np.testing.assert_allclose(ring_g, ring_ref, rtol=1e-5, atol=1e-12, err_msg="prefill rows")
+        assert np.all(ring_g[ring_ref == 0.0] == 0.0), "prefill rows: masked entries must be exactly 0"
+        # their sum must agree with the seed of the running-sum path
+        st.prefill_scores(q_tail)
+        np.testing.assert_allclose(_np64(_sub(st.score, seqs_t, heads_t)), ring_g.sum(axis=2), rtol=2e-6, atol=1e-12)
+        ring_o = ring_g.copy()
+    else:
+        ring_o = np.zeros((len(seqs), len(heads), R, wl.cap))
+    # whatever sits in unused slots of the ring must never be read
+    for s_i, L in enumerate(prompt["lengths"]):
+        ring[s_i, :, :, L:] = float("nan")
+    st.score.fill_(float("nan"))            # output only in this mode
+
+    host_len = list(prompt["lengths"])
+    for t in range(steps):
+        row = t % R
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        n_o = n_o + 1
+        sp_t = wl.sparsity_bp if sparsity_of_step is None else int(sparsity_of_step(t))
+        st.params.sparsity_bp = sp_t
+        if use_len_bound:
+            st.params.len_bound = max(host_len) + 1
+        ring_prev = _sub(ring, seqs_t, heads_t).cpu().numpy()
+        pos_prev = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
+        B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, R, row, st.score, st.pos,
+                                 st.cache_len, st.seq_len, st.kept_idx, st.kept_cnt, st.out, st.probs,
+                                 st.workspace)
+        st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
+        for s_i in range(wl.b):
+            host_len[s_i] = B.swa_budget(prompt["lengths"][s_i] + t + 1, host_len[s_i] + 1, wl.w, sp_t)[0]
+
+        q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
+        kept_o, cnt_o, out_o, p_o = O.decode_step_window(q_o, kn_o, vn_o, K_o, V_o, ring_o, row, score_o,
+                                                         pos_o, len_o, n_o, wl.w, sp_t, wl.scale)
+        kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
+        cnt_g = st.cache_len[seqs_t].cpu().numpy()
+        assert np.array_equal(cnt_g, cnt_o), f"step {t}: kept_cnt {cnt_g} vs {cnt_o}"
+        p32 = _sub(st.probs, seqs_t, heads_t).cpu().numpy().astype(np.float32)
+        comp32 = _sub(st.score, seqs_t, heads_t).cpu().numpy()
+        pos_post = _sub(st.pos, seqs_t, heads_t).cpu().numpy()
+        ring_post = _sub(ring, seqs_t, heads_t).cpu().numpy()
+        S32 = np.zeros(p32.shape, dtype=np.float32)
+        p_can = np.zeros_like(p32)
+        S_can = np.zeros_like(p32)
+        kept_can = np.full_like(kept_g, -1)
+        orders = {}
+        for i, m in enumerate(len_o):
+            # the kernel's sum: ring rows in index order, this step's weights in place of row `row`,
+            # nothing from earlier rows for the token appended now (slot m-1)
+            acc = np.zeros((len(heads), m), dtype=np.float32)
+            for j in range(R):
+                if j == row:
+                    term = p32[i, :, :m]
+                else:
+                    term = ring_prev[i, :, j, :m].copy()
+                    term[:, m - 1] = 0.0
+                acc = (acc + term).astype(np.float32)
+            S32[i, :, :m] = acc
+            c = cnt_g[i]
+            for hd in range(len(heads)):
+                assert np.array_equal(comp32[i, hd, :c], S32[i, hd, kept_g[i, hd, :c]]), \
+                    f"step {t}: compacted importance is not the fp32 row sum of the kept slots"
+                slot_pos = np.concatenate([pos_prev[i, hd, :m - 1], [n_o[i] - 1]])
+                order = np.argsort(slot_pos, kind="stable")
+                assert np.array_equal(slot_pos[order], pos_o[i, hd, :m]), f"step {t}: cached token set"
+                inv = np.empty(m, dtype=np.int64)
+                inv[order] = np.arange(m)
+                assert np.array_equal(slot_pos[kept_g[i, hd, :c]], pos_post[i, hd, :c]), \
+                    f"step {t}: kept_idx does not describe the compacted cache"
+                kept_can[i, hd, :c] = np.sort(inv[kept_g[i, hd, :c]])
+                p_can[i, hd, :m] = p32[i, hd, order]
+                S_can[i, hd, :m] = S32[i, hd, order]
+                orders[(i, hd)] = np.argsort(pos_post[i, hd, :c], kind="stable")
+        p_g, S_g = p_can.astype(np.float64), S_can.astype(np.float64)
+        out_g = _np64(_sub(st.out, seqs_t, heads_t))
+        for i, m in enumerate(len_o):
+            pe = np.abs(p_g[i, :, :m] - p_o[i, :, :m])
+            assert np.all(pe <= 1e-5 * np.abs(p_o[i, :, :m]) + 1e-12), f"step {t}: probs"
+            se = np.abs(S_g[i, :, :m] - score_o[i, :, :m])
+            assert np.all(se <= 1e-5 * np.abs(score_o[i, :, :m]) + 1e-12), f"step {t}: window sum"
+            rep.max_prob_rel = max(rep.max_prob_rel, float(np.max(pe / (np.abs(p_o[i, :, :m]) + 1e-30))))
+            rep.max_score_rel = max(rep.max_score_rel, float(np.max(se / (np.abs(score_o[i, :, :m]) + 1e-30))))
+        kept_ref, cnt_ref = O.select(S_g, len_o, n_o, wl.w, sp_t)
+        assert np.array_equal(cnt_ref, cnt_g)
+        for i, c in enumerate(cnt_g):
+            assert np.array_equal(kept_can[i, :, :c], kept_ref[i, :, :c]), \
+                f"step {t} seq {seqs[i]}: kept_idx differs from selection on the GPU's window sums"
+            for hd in range(len(heads)):
+                diff = set(kept_can[i, hd, :c].tolist()) ^ set(kept_o[i, hd, :c].tolist())
+                if diff:
+                    m = len_o[i]
+                    nl = O.budget(int(n_o[i]), int(m), wl.w, sp_t)[1]
+                    cutoff = np.sort(score_o[i, hd, :m - nl])[::-1][c - nl - 1]
+                    for j in diff:
+                        assert abs(score_o[i, hd, j] - cutoff) <= 2e-5 * abs(cutoff), f"step {t}: not a near tie"
+                    rep.near_tie_flips += len(diff) // 2
+            rep.evictions += (int(len_o[i]) - int(c)) * len(heads)
+        out_ref = O.sparse_attention(q_o, K_o, V_o, kept_can, cnt_g, wl.scale)
+        ea, er = check_out(out_g, out_ref, wl.dtype, f"step {t} out")
+        rep.max_out_abs, rep.max_out_rel = max(rep.max_out_abs, ea), max(rep.max_out_rel, er)
+
+        # adopt the GPU's row and sums, then compact both sides
+        for i, m in enumerate(len_o):
+            ring_o[i, :, row, :m] = p_g[i, :, :m]
+        score_o = S_g.copy()
+        O.compact_ring(ring_o, kept_can, cnt_g)
+        O.compact(K_o, V_o, score_o, pos_o, kept_can, cnt_g, len_o)
+        K_g = _np64(_sub(st.K, seqs_t, heads_t))
+        V_g = _np64(_sub(st.V, seqs_t, heads_t))
+        for (i, hd), o2 in orders.items():
+            L = len_o[i]
+            assert np.array_equal(K_g[i, hd, o2], K_o[i, hd, :L]), f"step {t}: K after compaction"
+            assert np.array_equal(V_g[i, hd, o2], V_o[i, hd, :L]), f"step {t}: V after compaction"
+            assert np.array_equal(pos_post[i, hd, o2], pos_o[i, hd, :L]), f"step {t}: pos after compaction"
+            assert np.array_equal(comp32[i, hd, o2].astype(np.float64), score_o[i, hd, :L])
+            assert np.array_equal(ring_post[i, hd][:, o2].astype(np.float64), ring_o[i, hd, :, :L]), \
+                f"step {t}: ring after compaction"
+        rep.steps += 1
+    assert st.check_status() == 0
+    return rep

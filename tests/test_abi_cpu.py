@@ -164,6 +164,29 @@ def test_compressed_cache_entry_points_validate_their_arguments(B):
     assert L.swa_quantize_kv(None, *([ok] * 7)) == B.SWA_ERR_NULL
 
 
+def test_strict_window_entry_points_validate_their_arguments(B):
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    pu = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED)
+    p0 = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16)
+
+    def step(p, ring=ok, R=4, row=0, cache_len=ctypes.c_void_p(0x2000)):
+        return L.swa_decode_step_window(ctypes.byref(p), ok, ok, ok, ok, ok, ring, R, row, ok, ok, cache_len,
+                                        ok, ok, ok, ok, ok, ok, ok)
+    assert step(p0) == B.SWA_ERR_BAD_SHAPE                      # only the unordered fused form
+    assert step(B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=7)) == B.SWA_ERR_BAD_SHAPE
+    assert step(pu, ring=None) == B.SWA_ERR_NULL
+    assert step(pu, R=0) == B.SWA_ERR_BAD_SHAPE
+    assert step(pu, R=B.SWA_MAX_WINDOW_ROWS + 1) == B.SWA_ERR_BAD_SHAPE
+    assert step(pu, R=4, row=4) == B.SWA_ERR_BAD_SHAPE
+    assert step(pu, R=4, row=-1) == B.SWA_ERR_BAD_SHAPE
+    assert step(pu, cache_len=ok) == B.SWA_ERR_BAD_SHAPE        # cache_len == kept_cnt
+    assert L.swa_prefill_rows(ctypes.byref(p0), ok, 0, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
+    assert L.swa_prefill_rows(ctypes.byref(p0), ok, B.SWA_MAX_WINDOW_ROWS + 1, ok, ok, ok, ok, ok) == B.SWA_ERR_BAD_SHAPE
+    assert L.swa_prefill_rows(ctypes.byref(p0), ok, 4, ok, ok, None, ok, ok) == B.SWA_ERR_NULL
+    assert L.swa_prefill_rows(ctypes.byref(p0), ctypes.c_void_p(0x1004), 4, ok, ok, ok, ok, ok) == B.SWA_ERR_ALIGNMENT
+
+
 def test_binding_fails_loudly_without_the_library(B, monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

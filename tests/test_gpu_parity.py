@@ -228,6 +228,31 @@ def SW_EVEN(B):
     return B.SWA_W_EVEN_SPLIT
 
 
+def test_strict_window_sum_matches_the_oracle(env):
+    # Algorithm 1 line 2 to the letter: importance = sum of the last R attention rows (a ring)
+    O, B, W, LS = env
+    _say("strict window, small shapes")
+    for dtype, d, R, w in [("f32", 64, 4, 8), ("f16", 128, 16, 7), ("bf16", 128, 5, 0), ("f16", 64, 1, 3)]:
+        wl = W.Workload(f"t_win_{dtype}_{R}", 39, b=3, h=3, d=d, dtype=dtype, prompt_lo=2, prompt_hi=300,
+                        steps=3 * R + 5, w=w, sparsity_bp=7000, hh_frac=0.02)
+        _say(f"  {dtype} d={d} R={R}")
+        rep = LS.run_lockstep_window(wl, R)
+        assert rep.evictions > 0
+    rep = LS.run_lockstep_window(W.CONFIGS["c1_tiny"], 8, seed_rows=False)
+    assert rep.steps == 16
+    # budget that tightens and relaxes: many evictions at once on a cache out of token order
+    wl = W.Workload("t_win_sched", 40, b=2, h=4, d=128, dtype="f16", prompt_lo=60, prompt_hi=90,
+                    steps=24, w=4, sparsity_bp=3000, hh_frac=0.02)
+    LS.run_lockstep_window(wl, 6, sparsity_of_step=lambda t: 3000 if t < 10 else (8500 if t < 12 else 6000))
+    wl = W.Workload("t_win_even", 41, b=2, h=2, d=128, dtype="f16", prompt_lo=100, prompt_hi=140,
+                    steps=20, w=B.SWA_W_EVEN_SPLIT, sparsity_bp=8000, hh_frac=0.02)
+    LS.run_lockstep_window(wl, 8)
+    _say("strict window, config 2 at full size (R = w = 16), every pair")
+    rep = LS.run_lockstep_window(W.CONFIGS["c2_opt6p7b"], 16, use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
