@@ -399,7 +399,9 @@ def main():
     # rocprofv3's per-kernel average (profiles/).  Split mode: per-launch event brackets.
     dec_ms = res["ms_per_step"] if fused else res["decode_kernel_ms_avg"]
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
-    traffic = load_traffic(wl.name) if args.step_mode == "unordered" and not args.kv_int8 else None
+    # measured traffic is stored per (workload, way of issuing the step)
+    tag = ("" if args.step_mode == "unordered" else "_" + args.step_mode) + ("_q8" if args.kv_int8 else "")
+    traffic = load_traffic(wl.name + tag) if args.step_mode in ("unordered", "fused", "window") else None
     line = {
         "metric": "SWA decode-step KV tokens/s",
         "value": res["kv_tokens_per_s"],
@@ -419,7 +421,9 @@ def main():
                                       "head-summed importance, hole-filling compaction)",
                             "window": "swa_decode_step_window (strict local attention sum over min(w, 64) rows, "
                                       "hole-filling compaction)",
-                            "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]},
+                            "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]
+                           + ("; 8-bit compressed cache (swa_quantize_kv once, then swa_decode_step_q8)"
+                              if args.kv_int8 else "")},
         "roofline": {
             "bound": "hbm", "kernel": "swa_decode_kernel",
             "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
