@@ -75,7 +75,8 @@ __device__ __forceinline__ void merge_stats(float& M, float& L, float M2, float 
     L = a + b;
 }
 
-template <typename T, int D, int RT>
+// WR: also write the R rows themselves (the ring of the strict local attention sum).
+template <typename T, int D, int RT, bool WR>
 __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
 {
     constexpr int NT = 256;
@@ -100,7 +101,7 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     int s = a.cache_len[pair / a.h];
     s = s > cap ? cap : s;
     float* Sp = a.score ? a.score + pair * (int64_t)cap : nullptr;
-    float* Rp = a.rows ? a.rows + pair * (int64_t)R * cap : nullptr;
+    float* Rp = WR ? a.rows + pair * (int64_t)R * cap : nullptr;
 
     if (s <= 0) {
         if (Sp)
@@ -232,7 +233,9 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
                     const bool vis = (r < R) && (key <= t_off + r);
                     const float p = __builtin_amdgcn_exp2f(c[4 * g + j] * a.scale_log2e - Mr[j]) * Ir[j];
                     colsum += vis ? p : 0.f;
-                    if (Rp && r < R && key < s) Rp[(int64_t)r * cap + key] = vis ? p : 0.f;
+                    if constexpr (WR) {
+                        if (r < R && key < s) Rp[(int64_t)r * cap + key] = vis ? p : 0.f;
+                    }
                 }
             }
         }
@@ -260,12 +263,21 @@ template <typename T, int D>
 static int launch_prefill_t(const PrefillArgs& a, int64_t pairs, hipStream_t stream)
 {
     const int rt = (a.R + 31) / 32;
-    switch (rt) {
-        case 1: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 1>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
-        case 2: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 2>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
-        case 3: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 3>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
-        case 4: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 4>), dim3((unsigned)pairs), dim3(256), 0, stream, a); break;
-        default: return SWA_ERR_BAD_SHAPE;
+    const dim3 grid((unsigned)pairs), block(256);
+    if (a.rows) {
+        switch (rt) {
+            case 1: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 1, true>), grid, block, 0, stream, a); break;
+            case 2: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 2, true>), grid, block, 0, stream, a); break;
+            default: return SWA_ERR_BAD_SHAPE;
+        }
+    } else {
+        switch (rt) {
+            case 1: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 1, false>), grid, block, 0, stream, a); break;
+            case 2: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 2, false>), grid, block, 0, stream, a); break;
+            case 3: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 3, false>), grid, block, 0, stream, a); break;
+            case 4: hipLaunchKernelGGL((swa_prefill_kernel<T, D, 4, false>), grid, block, 0, stream, a); break;
+            default: return SWA_ERR_BAD_SHAPE;
+        }
     }
     return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
 }
