@@ -394,6 +394,81 @@ def test_capacity_overflow_is_reported_and_nothing_is_written(env):
     assert st.check_status() == B.SWA_ERR_CAPACITY
 
 
+def test_compressed_cache_and_strict_window_edge_cases(env):
+    O, B, W, LS = env
+    # exact ties on a compressed cache: identical prompt keys give identical codes (flat channels
+    # take the minimum range), so the tie rule decides every eviction
+    wl = W.Workload("t_q8_ties", 42, b=2, h=3, d=128, dtype="f16", prompt_lo=40, prompt_hi=70,
+                    steps=20, w=3, sparsity_bp=5000, hh_frac=0.02)
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    for s_i, L in enumerate(prompt["lengths"]):
+        prompt["K"][s_i, :, :L] = prompt["K"][s_i, :, :1].clone()
+    rep = LS.run_lockstep(wl, prompt=prompt, fused=True, unordered=True, kv_int8=True)
+    assert rep.evictions > 0
+    # a full cache is skipped and reported by both new step entry points; nothing of it is written
+    b, h, d, cap, R = 3, 2, 128, 32, 4
+    for mode in ("q8", "window"):
+        flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+        params = B.make_params(b, h, d, cap, 2, 5000, torch.float16, flags=flags)
+        st = B.DecodeState(params)
+        st.K.normal_()
+        st.V.normal_()
+        lens = torch.tensor([5, 32, 31], dtype=torch.int32, device="cuda")   # sequence 1 is full
+        st.cache_len.copy_(lens)
+        st.seq_len.copy_(lens + 1)
+        st.pos[:] = torch.arange(cap, device="cuda", dtype=torch.int32)
+        x = torch.randn((b, h, d), device="cuda").half()
+        ring = torch.rand((b, h, R, cap), device="cuda")
+        if mode == "q8":
+            st.quantize()
+        K0, V0, s0, r0 = st.K.clone(), st.V.clone(), st.score.clone(), ring.clone()
+        if mode == "q8":
+            st.decode_compact_step(x, x, x)
+        else:
+            B.swa_decode_step_window(st.params, x, x, x, st.K, st.V, ring, R, 1, st.score, st.pos, st.cache_len,
+                                     st.seq_len, st.kept_idx, st.kept_cnt, st.out, None, st.workspace)
+            st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
+        assert st.check_status() == B.SWA_ERR_CAPACITY
+        keep0 = B.swa_budget(6, 6, 2, 5000)[0]
+        keep2 = B.swa_budget(32, 32, 2, 5000)[0]
+        assert st.cache_len.tolist() == [keep0, 32, keep2], mode
+        assert torch.equal(st.K[1], K0[1]) and torch.equal(st.V[1], V0[1]) and torch.equal(st.score[1], s0[1])
+        assert torch.equal(ring[1], r0[1])
+    # both paths give the same bits on a second run
+    wl = W.Workload("t_det2", 43, b=3, h=4, d=128, dtype="f16", prompt_lo=100, prompt_hi=300,
+                    steps=6, w=8, sparsity_bp=8000, hh_frac=0.02)
+    for mode in ("q8", "window"):
+        results = []
+        for _ in range(2):
+            prompt = W.make_prompt(wl, "cuda", slack="nan")
+            st = LS.new_state(wl, prompt, debug_probs=False)
+            st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+            st.score.zero_()
+            ring = torch.zeros((wl.b, wl.h, 8, wl.cap), device="cuda")
+            if mode == "q8":
+                st.quantize()
+            outs = []
+            for t in range(wl.steps):
+                q, kn, vn = W.make_step(wl, t, prompt["mu"])
+                st.seq_len += 1
+                if mode == "q8":
+                    st.decode_compact_step(q, kn, vn)
+                else:
+                    B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, 8, t % 8, st.score, st.pos,
+                                             st.cache_len, st.seq_len, st.kept_idx, st.kept_cnt, st.out, None,
+                                             st.workspace)
+                    st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
+                outs.append(st.out.clone())
+            assert not torch.isnan(torch.stack(outs)).any()
+            L = st.cache_len.tolist()
+            results.append((torch.stack(outs), [st.score[s, :, :L[s]].clone() for s in range(wl.b)],
+                            [st.pos[s, :, :L[s]].clone() for s in range(wl.b)], L))
+        a, b_ = results
+        assert torch.equal(a[0], b_[0]) and a[3] == b_[3], mode
+        for s in range(wl.b):
+            assert torch.equal(a[1][s], b_[1][s]) and torch.equal(a[2][s], b_[2][s]), mode
+
+
 def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
     O, B, W, LS = env
     wl = W.Workload("t_det", 15, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=400,
