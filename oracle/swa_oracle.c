@@ -470,6 +470,54 @@ int swa_oracle_prefill_scores(int32_t b, int32_t h, int32_t d, int32_t cap, int3
 
 
 /* ------------------------------------------------------------------------ */
+/* Prefill attention: Eq. 1-2 over the whole prompt with the causal mask     */
+/* (the grey upper triangle of the attention-weight figures).  For every     */
+/* pair and every prompt position t < s = cache_len:                         */
+/*   out[t] = sum_{j<=t} softmax_{j<=t}(q_t . k_j * scale) v_j.              */
+/* Q and out are [b, h, cap, d] like the caches; rows >= s are left alone.   */
+/* ------------------------------------------------------------------------ */
+int swa_oracle_prefill_attention(int32_t b, int32_t h, int32_t d, int32_t cap, double scale,
+                                 const double *Q, const double *K, const double *V,
+                                 const int32_t *cache_len, double *out)
+{
+    int64_t pairs = (int64_t)b * h;
+    int failed = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(| : failed)
+    for (int64_t pair = 0; pair < pairs; ++pair) {
+        int32_t s = cache_len[pair / h];
+        double *aw = (double *)malloc(sizeof(double) * (size_t)(s > 0 ? s : 1));
+        if (!aw) {
+            failed = 1;
+            continue;
+        }
+        for (int32_t t = 0; t < s; ++t) {
+            const double *qt = Q + (pair * cap + t) * d;
+            double zmax = -INFINITY;
+            for (int32_t j = 0; j <= t; ++j) {
+                double z = 0.0;
+                for (int32_t c = 0; c < d; ++c) z += qt[c] * K[(pair * cap + j) * d + c];
+                aw[j] = z * scale;
+                if (aw[j] > zmax) zmax = aw[j];
+            }
+            double denom = 0.0;
+            for (int32_t j = 0; j <= t; ++j) {
+                aw[j] = exp(aw[j] - zmax);
+                denom += aw[j];
+            }
+            double *o = out + (pair * cap + t) * d;
+            for (int32_t c = 0; c < d; ++c) o[c] = 0.0;
+            for (int32_t j = 0; j <= t; ++j) {
+                double p = aw[j] / denom;
+                for (int32_t c = 0; c < d; ++c) o[c] += p * V[(pair * cap + j) * d + c];
+            }
+        }
+        free(aw);
+    }
+    return failed ? SWA_ORACLE_ERR_ALLOC : SWA_ORACLE_OK;
+}
+
+
+/* ------------------------------------------------------------------------ */
 /* Strict local attention sum (Alg. 1 line 2 taken literally): S is the sum  */
 /* of the R most recent rows of the attention-weight matrix and nothing      */
 /* older.  The rows are kept per pair in ring [b, h, R, cap]: ring row j     */

@@ -262,3 +262,13 @@ def decode_step_window(q, k_new, v_new, K, V, ring, row: int, score, pos, cache_
         _pi(kept_idx), _pi(kept_cnt), _pd(out), _pd(p))
     _check(rc, "decode_step_window")
     return kept_idx, kept_cnt, out, p
+
+
+def prefill_attention(Q, K, V, cache_len, scale: float):
+    """Causal attention over the prompt: Q, K, V [b,h,cap,d] -> out [b,h,cap,d] (rows >= cache_len zero)."""
+    b, h, d, cap = _dims(K)
+    out = np.zeros(K.shape, dtype=np.float64)
+    rc = lib().swa_oracle_prefill_attention(b, h, d, cap, ctypes.c_double(scale), _pd(_f64(Q)), _pd(K),
+                                            _pd(V), _pi(_i32(cache_len)), _pd(out))
+    _check(rc, "prefill_attention")
+    return out

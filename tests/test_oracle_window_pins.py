@@ -139,3 +139,41 @@ def test_window_mass_without_eviction_is_the_number_of_rows(oracle):
         kept, cnt, out, p = O.decode_step_window(q, kn, vn, K, V, ring, t % R, score, pos, lens, n, 3, 0, 0.5)
         assert cnt[0] == lens[0]                                   # sparsity 0: nothing leaves
         np.testing.assert_allclose(score[0, 0, :lens[0]].sum(), min(t + 1, R), rtol=1e-12)
+
+
+def test_prefill_attention_is_causal_dense_attention(oracle):
+    """Eq. 1-2 with the causal mask: every row against the library softmax; the last row against the
+    oracle's own decode step at sparsity 0 (an independent path); no dependence on later tokens."""
+    O = oracle
+    rng = np.random.default_rng(16)
+    b, h, cap, d = 2, 2, 24, 5
+    K, V, pos, lens = _state(rng, b, h, cap, d, [19, 7])
+    Q = rng.standard_normal((b, h, cap, d))
+    out = O.prefill_attention(Q, K, V, lens, 0.45)
+    for s in range(b):
+        L = lens[s]
+        assert np.all(out[s, :, L:] == 0)
+        for hd in range(h):
+            np.testing.assert_allclose(out[s, hd, 0], V[s, hd, 0], rtol=1e-13)     # one visible token
+            for t in range(L):
+                a = softmax(K[s, hd, :t + 1] @ Q[s, hd, t] * 0.45)
+                np.testing.assert_allclose(out[s, hd, t], a @ V[s, hd, :t + 1], rtol=1e-12, atol=1e-14)
+    # the last prompt row is a decode step over the first s-1 tokens plus the last one, nothing evicted
+    Kc, Vc = K.copy(), V.copy()
+    score = np.zeros((b, h, cap))
+    pc = pos.copy()
+    lm1 = lens - 1
+    kn = np.stack([K[s, :, lens[s] - 1] for s in range(b)])
+    vn = np.stack([V[s, :, lens[s] - 1] for s in range(b)])
+    qn = np.stack([Q[s, :, lens[s] - 1] for s in range(b)])
+    _, _, o_dec, _ = O.decode_step(qn, kn, vn, Kc, Vc, score, pc, lm1.copy(), lens, 3, 0, 0.45)
+    for s in range(b):
+        np.testing.assert_allclose(out[s, :, lens[s] - 1], o_dec[s], rtol=1e-12, atol=1e-14)
+    # causality: changing everything from position 5 on leaves rows 0..4 alone
+    K2, V2, Q2 = K.copy(), V.copy(), Q.copy()
+    K2[:, :, 5:] += 1.0
+    V2[:, :, 5:] -= 2.0
+    Q2[:, :, 5:] *= 3.0
+    out2 = O.prefill_attention(Q2, K2, V2, lens, 0.45)
+    assert np.array_equal(out2[:, :, :5], out[:, :, :5])
+    assert not np.allclose(out2[0, :, 5:19], out[0, :, 5:19])
