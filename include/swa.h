@@ -275,6 +275,22 @@ int swa_decode_step_window(const swa_params *params, const void *q, const void *
                            const int32_t *seq_len, int32_t *kept_idx, int32_t *kept_cnt, void *out,
                            float *probs_dbg, void *workspace, void *stream);
 
+/*
+ * Prefill: dense causal attention over the whole prompt (Eq. 1-2 with the causal mask) plus the
+ * importance seed of swa_prefill_scores, for fp16 and bf16.  For every pair and every prompt
+ * position t < cache_len[s]:
+ *   out[t] = sum_{j<=t} softmax_{j<=t}(q[t] . K[j] * scale) V[j], rounded once to dtype;
+ * if R > 0, score gets the column sums of the last R rows of that attention-weight matrix
+ * (queries q[cache_len-R .. cache_len-1]), exactly as swa_prefill_scores would with those rows.
+ * Runs on MFMA (flash-style: the s x s weight matrix is never stored).
+ *   q, out [b,h,cap,d] dtype (rows >= cache_len are neither read nor written);
+ *   k_cache, v_cache (in); cache_len [b] (in); 0 <= R <= SWA_MAX_PREFILL_ROWS;
+ *   score [b,h,cap] (out) or NULL when R == 0.  params->len_bound, if set, bounds cache_len.
+ */
+int swa_prefill_attention(const swa_params *params, const void *q, const void *k_cache,
+                          const void *v_cache, const int32_t *cache_len, void *out, int32_t R,
+                          float *score, void *workspace, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

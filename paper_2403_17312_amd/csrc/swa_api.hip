@@ -187,7 +187,7 @@ int swa_prefill_scores(const swa_params* params, const void* q_tail, int32_t R, 
     if (!q_tail || !k_cache || !cache_len || !score) return SWA_ERR_NULL;
     if (R < 1 || R > SWA_MAX_PREFILL_ROWS) return SWA_ERR_BAD_SHAPE;
     if (!swa::aligned16(q_tail) || !swa::aligned16(k_cache)) return SWA_ERR_ALIGNMENT;
-    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, score, nullptr,
+    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, score, nullptr, false,
                                static_cast<hipStream_t>(stream));
 }
 
@@ -201,7 +201,7 @@ int swa_prefill_rows(const swa_params* params, const void* q_tail, int32_t R, co
     if (!q_tail || !k_cache || !cache_len || !ring) return SWA_ERR_NULL;
     if (R < 1 || R > SWA_MAX_WINDOW_ROWS) return SWA_ERR_BAD_SHAPE;
     if (!swa::aligned16(q_tail) || !swa::aligned16(k_cache)) return SWA_ERR_ALIGNMENT;
-    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, nullptr, ring,
+    return swa::launch_prefill(*params, swa::effective_scale(params), q_tail, R, k_cache, cache_len, nullptr, ring, false,
                                static_cast<hipStream_t>(stream));
 }
 
@@ -226,6 +226,25 @@ static int decode_common(const swa_params* params, const void* q, const void* k_
     return swa::launch_decode(*params, swa::effective_scale(params), q, k_new, v_new, k_cache, v_cache, score,
                               pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, qparams, ring,
                               ring_rows, ring_row, static_cast<hipStream_t>(stream));
+}
+
+int swa_prefill_attention(const swa_params* params, const void* q, const void* k_cache, const void* v_cache,
+                          const int32_t* cache_len, void* out, int32_t R, float* score, void* workspace,
+                          void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    (void)workspace;
+    if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (params->dtype != SWA_F16 && params->dtype != SWA_BF16) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (!q || !k_cache || !v_cache || !cache_len || !out) return SWA_ERR_NULL;
+    if (R < 0 || R > SWA_MAX_PREFILL_ROWS || (R > 0 && !score)) return R > 0 && !score ? SWA_ERR_NULL : SWA_ERR_BAD_SHAPE;
+    if (!swa::aligned16(q) || !swa::aligned16(k_cache) || !swa::aligned16(v_cache) || !swa::aligned16(out))
+        return SWA_ERR_ALIGNMENT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    rc = swa::launch_flash_prefill(*params, swa::effective_scale(params), q, k_cache, v_cache, cache_len, out, st);
+    if (rc != SWA_OK || R == 0) return rc;
+    return swa::launch_prefill(*params, swa::effective_scale(params), q, R, k_cache, cache_len, score, nullptr, true, st);
 }
 
 int swa_decode_step_window(const swa_params* params, const void* q, const void* k_new, const void* v_new,

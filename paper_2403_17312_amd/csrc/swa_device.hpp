@@ -211,6 +211,44 @@ struct QFrag<Q8> {
     }
 };
 
+// One 32x32 MFMA step over a 16-byte operand vector per lane: lane l supplies row (l % 32) of its
+// operand and the k-slice (l / 32); the fp32 result gives lane l column (l % 32) and rows
+// 8*(i/4) + 4*(l/32) + (i%4), i = 0..15.
+template <typename T>
+struct Mfma;
+template <>
+struct Mfma<F16> {
+    static constexpr int kElemsPerIssue = 8;
+    // one issue consumes a whole 16-byte vector
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
+                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mfma<BF16> {
+    static constexpr int kElemsPerIssue = 8;
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
+                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
+    }
+};
+template <>
+struct Mfma<F32> {
+    static constexpr int kElemsPerIssue = 1;
+    // four issues per 16-byte vector, one fp32 element each
+    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
+    {
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.x), u2f(b.x), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.y), u2f(b.y), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.z), u2f(b.z), c, 0, 0, 0);
+        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.w), u2f(b.w), c, 0, 0, 0);
+        return c;
+    }
+};
+
 // Round fp32 values to the cache dtype and pack them into one 16-byte vector.
 template <typename T>
 __device__ __forceinline__ Vec16 pack(const float* f);

@@ -1,0 +1,230 @@
+// Prefill attention on MFMA: Eq. 1-2 over the whole prompt with the causal mask,
+//   out[t] = sum_{j<=t} softmax_{j<=t}(q_t . k_j * scale) v_j      for every prompt position t.
+// One workgroup (4 waves) per (pair, block of 128 queries); a wave owns 32 queries.  The
+// attention-weight matrix is never stored: key tiles of 32 stream through LDS (double-buffered,
+// loaded to registers one tile ahead), and every wave keeps flash-style running (max, sum,
+// output) state for its queries.
+//
+// Both contractions are arranged so that a lane owns ONE query throughout:
+//   S^T = K Q^T     A = key tile (LDS, row-major), B = query fragments (registers)
+//                   -> lane l holds, for query l%32, the logits of 16 of the tile's keys;
+//   O^T = V^T P^T   A = value tile transposed in LDS, B = the lane's own 16 weights, packed
+//                   -> lane l holds, for query l%32, 16 channels of every 32-channel tile.
+// So the row statistics, the rescaling of the running output and the weights that feed the
+// second product never leave the lane (one exchange with the other half-wave for the maximum).
+// The 16 keys a lane holds are keys 8*(i/4) + 4*(l/32) + (i%4) of the tile; the value tile is
+// written to LDS transposed AND with its keys in that order, so a value fragment is one 16-byte
+// LDS read and the contraction pairs every weight with its own key.
+#include "swa_kernels.hpp"
+
+namespace swa {
+
+struct FlashArgs {
+    const char* q;
+    const char* k;
+    const char* v;
+    char* out;
+    const int32_t* cache_len;
+    int32_t h, cap;
+    float scale_log2e;
+};
+
+// Half-precision element e (0..7) of a 16-byte vector, in the low 16 bits.
+__device__ __forceinline__ uint32_t half_of(const Vec16& v, int e)
+{
+    const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+    return (w[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
+}
+
+// Two fp32 values rounded to T, packed into one dword.
+template <typename T>
+__device__ __forceinline__ uint32_t pack2(float f0, float f1);
+template <>
+__device__ __forceinline__ uint32_t pack2<F16>(float f0, float f1)
+{
+    return f32_to_f16_bits(f0) | (f32_to_f16_bits(f1) << 16);
+}
+template <>
+__device__ __forceinline__ uint32_t pack2<BF16>(float f0, float f1)
+{
+    return f32_to_bf16_bits(f0) | (f32_to_bf16_bits(f1) << 16);
+}
+
+template <typename T, int D>
+__global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
+{
+    constexpr int NT = 256;
+    constexpr int ROWB = D * 2;
+    constexpr int NV = D / 16;          // 16-byte vectors a lane supplies for a 32-row operand
+    constexpr int CT = D / 32;          // 32-channel tiles of the output
+    constexpr int BK = 32;              // keys per tile
+    constexpr int BQ = 128;             // queries per workgroup
+    constexpr int KSTR = ROWB + 16;     // LDS row of the key tile, padded against bank conflicts
+    constexpr int VSTR = BK * 2 + 16;   // LDS row (one channel, 32 keys) of the transposed value tile
+    constexpr int CPR = ROWB / 16;      // 16-byte chunks per cache row
+    constexpr int LD = BK * CPR / NT;   // chunks per thread, per tensor and tile
+    static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
+
+    __shared__ __align__(16) char s_k[2][BK * KSTR];
+    __shared__ __align__(16) char s_vt[2][D * VSTR];
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = tid >> 6;
+    const int l32 = lane & 31;
+    const int hb = lane >> 5;
+    const int64_t pair = blockIdx.x;
+    int s = a.cache_len[pair / a.h];
+    s = s > a.cap ? a.cap : s;
+    const int qb = (int)gridDim.y - 1 - (int)blockIdx.y;   // longest blocks first
+    const int q0 = qb * BQ;
+    if (q0 >= s) return;
+
+    const char* Qp = a.q + pair * (int64_t)a.cap * ROWB;
+    const char* Kp = a.k + pair * (int64_t)a.cap * ROWB;
+    const char* Vp = a.v + pair * (int64_t)a.cap * ROWB;
+    char* Op = a.out + pair * (int64_t)a.cap * ROWB;
+
+    const int t = q0 + wave * 32 + l32;          // this lane's query position
+    const int tq = t < s ? t : s - 1;            // lanes past the prompt shadow the last query
+    Vec16 qv[NV];
+#pragma unroll
+    for (int v = 0; v < NV; ++v) qv[v] = load16(Qp + (int64_t)tq * ROWB + v * 32 + hb * 16);
+
+    const int q_hi = (q0 + BQ < s ? q0 + BQ : s) - 1;    // last query of the workgroup
+    const int nkt = q_hi / BK + 1;                        // key tiles 0..nkt-1 cover keys 0..q_hi
+    const int w_lo = q0 + wave * 32;
+    const int w_hi = (w_lo + 31 < s - 1) ? w_lo + 31 : s - 1;
+    const int my_last = (w_lo < s) ? w_hi / BK : -1;      // last tile with a visible key for this wave
+
+    Vec16 gk[LD], gv[LD];
+    auto gload = [&](int kt) {
+#pragma unroll
+        for (int x = 0; x < LD; ++x) {
+            const int id = tid + x * NT;
+            const int j = id / CPR, cc = id % CPR;
+            int row = kt * BK + j;
+            row = row < s ? row : s - 1;          // rows past the prompt are masked; keep them finite
+            gk[x] = load16(Kp + (int64_t)row * ROWB + cc * 16);
+            gv[x] = load16(Vp + (int64_t)row * ROWB + cc * 16);
+        }
+    };
+    auto lstore = [&](int buf) {
+#pragma unroll
+        for (int x = 0; x < LD; ++x) {
+            const int id = tid + x * NT;
+            const int j = id / CPR, cc = id % CPR;
+            store16(s_k[buf] + j * KSTR + cc * 16, gk[x]);
+            // key j is element i16 of half-wave hbk's 16 keys: its place in the channel's row
+            const int i16 = 4 * (j / 8) + (j % 4);
+            const int hbk = (j / 4) % 2;
+            const int posk = ((i16 / 8) * 2 + hbk) * 8 + (i16 % 8);
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<uint16_t*>(s_vt[buf] + (cc * 8 + e) * VSTR + posk * 2) = (uint16_t)half_of(gv[x], e);
+        }
+    };
+
+    float16_t o[CT];
+#pragma unroll
+    for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) o[ct][i] = 0.f;
+    float m = -INFINITY, l = 0.f;
+
+    gload(0);
+    lstore(0);
+    __syncthreads();
+    for (int kt = 0; kt < nkt; ++kt) {
+        const int buf = kt & 1;
+        if (kt + 1 < nkt) gload(kt + 1);
+        if (kt <= my_last) {
+            float16_t c;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) c[i] = 0.f;
+            const char* kb = s_k[buf] + l32 * KSTR + hb * 16;
+#pragma unroll
+            for (int v = 0; v < NV; ++v) c = Mfma<T>::run(load16(kb + v * 32), qv[v], c);   // C[key][query]
+            float z[16];
+            float mx = -INFINITY;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                const int key = kt * BK + 8 * (i / 4) + 4 * hb + (i % 4);
+                z[i] = (key <= tq) ? c[i] * a.scale_log2e : -INFINITY;
+                mx = fmaxf(mx, z[i]);
+            }
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            // tile 0 holds key 0, visible to every query, so the running maximum is finite from
+            // the first tile on
+            const float m_new = fmaxf(m, mx);
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);     // 0 on the first tile
+            float p[16];
+            float ps = 0.f;
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);           // 0 for masked keys
+                ps += p[i];
+            }
+            l = l * alpha + ps;
+            m = m_new;
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[ct][i] *= alpha;
+            const Vec16 p0 = pack<T>(p), p1 = pack<T>(p + 8);
+#pragma unroll
+            for (int ct = 0; ct < CT; ++ct) {
+                const char* vb = s_vt[buf] + (ct * 32 + l32) * VSTR + hb * 16;
+                o[ct] = Mfma<T>::run(load16(vb), p0, o[ct]);                                  // C[channel][query]
+                o[ct] = Mfma<T>::run(load16(vb + 32), p1, o[ct]);
+            }
+        }
+        if (kt + 1 < nkt) lstore(buf ^ 1);
+        __syncthreads();
+    }
+
+    l += __shfl_xor(l, 32, kWave);
+    if (t < s) {
+        const float inv = 1.f / l;
+#pragma unroll
+        for (int ct = 0; ct < CT; ++ct) {
+#pragma unroll
+            for (int g = 0; g < 4; ++g) {
+                // channels 32 ct + 8 g + 4 hb + 0..3 of query t
+                uint32_t w[2];
+#pragma unroll
+                for (int r = 0; r < 2; ++r)
+                    w[r] = pack2<T>(o[ct][4 * g + 2 * r] * inv, o[ct][4 * g + 2 * r + 1] * inv);
+                *reinterpret_cast<uint2*>(Op + (int64_t)t * ROWB + (32 * ct + 8 * g + 4 * hb) * 2) = make_uint2(w[0], w[1]);
+            }
+        }
+    }
+}
+
+int launch_flash_prefill(const swa_params& p, float scale, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* cache_len, void* out, hipStream_t stream)
+{
+    FlashArgs a;
+    a.q = static_cast<const char*>(q);
+    a.k = static_cast<const char*>(k_cache);
+    a.v = static_cast<const char*>(v_cache);
+    a.out = static_cast<char*>(out);
+    a.cache_len = cache_len;
+    a.h = p.h;
+    a.cap = p.cap;
+    a.scale_log2e = scale * 1.44269504088896340736f;
+    const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
+    const dim3 grid((unsigned)((int64_t)p.b * p.h), (unsigned)((bound + 127) / 128));
+    if (p.dtype == SWA_F16) {
+        if (p.d == 64) hipLaunchKernelGGL((swa_flash_prefill_kernel<F16, 64>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((swa_flash_prefill_kernel<F16, 128>), grid, dim3(256), 0, stream, a);
+    } else if (p.dtype == SWA_BF16) {
+        if (p.d == 64) hipLaunchKernelGGL((swa_flash_prefill_kernel<BF16, 64>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((swa_flash_prefill_kernel<BF16, 128>), grid, dim3(256), 0, stream, a);
+    } else {
+        return SWA_ERR_UNSUPPORTED_DTYPE;
+    }
+    return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
+}
+
+}  // namespace swa

@@ -47,6 +47,10 @@ int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* sco
                    hipStream_t stream);
 
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
-                   const int32_t* cache_len, float* score, float* rows, hipStream_t stream);
+                   const int32_t* cache_len, float* score, float* rows, bool q_in_place, hipStream_t stream);
+
+// Causal attention over the whole prompt (Eq. 1-2) on MFMA: out[t] for every prompt position.
+int launch_flash_prefill(const swa_params& p, float scale, const void* q, const void* k_cache, const void* v_cache,
+                         const int32_t* cache_len, void* out, hipStream_t stream);
 
 }  // namespace swa

@@ -26,42 +26,9 @@ struct PrefillArgs {
     float* score;   // column sums over the R rows, or NULL
     float* rows;    // [b,h,R,cap] the R rows themselves, or NULL
     int32_t h, cap, R;
+    int32_t q_in_place;   // 0: q_tail is [b,h,R,d]; 1: it is the whole prompt's [b,h,cap,d] and the
+                          //    R rows are the ones at positions cache_len-R .. cache_len-1
     float scale_log2e;
-};
-
-template <typename T>
-struct Mfma;
-template <>
-struct Mfma<F16> {
-    static constexpr int kElemsPerIssue = 8;
-    // one issue consumes a whole 16-byte vector
-    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(half8_t, a),
-                                                      __builtin_bit_cast(half8_t, b), c, 0, 0, 0);
-    }
-};
-template <>
-struct Mfma<BF16> {
-    static constexpr int kElemsPerIssue = 8;
-    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                       __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-    }
-};
-template <>
-struct Mfma<F32> {
-    static constexpr int kElemsPerIssue = 1;
-    // four issues per 16-byte vector, one fp32 element each
-    static __device__ __forceinline__ float16_t run(const Vec16& a, const Vec16& b, float16_t c)
-    {
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.x), u2f(b.x), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.y), u2f(b.y), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.z), u2f(b.z), c, 0, 0, 0);
-        c = __builtin_amdgcn_mfma_f32_32x32x2f32(u2f(a.w), u2f(b.w), c, 0, 0, 0);
-        return c;
-    }
 };
 
 // Merge two (max, sum-of-exp2) pairs of disjoint key sets.
@@ -112,7 +79,8 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     }
 
     const char* Kp = a.k_cache + pair * (int64_t)cap * ROWB;
-    const char* Qp = a.q_tail + pair * (int64_t)R * ROWB;
+    const int qbase = a.q_in_place ? s - R : 0;   // row index of query 0 (negative: rows before the prompt)
+    const char* Qp = a.q_tail + pair * (int64_t)(a.q_in_place ? cap : R) * ROWB;
 
     // Lane (row, hb) supplies the 16-byte chunks 2v + hb, v = 0..NV-1, of its row: the two
     // half-wave lanes of a row read adjacent chunks, and query and key fragments use the same
@@ -126,7 +94,8 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
         const int r = rt * 32 + l32;
 #pragma unroll
         for (int v = 0; v < NV; ++v) {
-            qv[rt][v] = (r < R) ? load16(Qp + (int64_t)r * ROWB + v * 32 + lane_off)
+            const int qrow = qbase + r > 0 ? qbase + r : 0;          // rows before the prompt are masked below
+            qv[rt][v] = (r < R) ? load16(Qp + (int64_t)qrow * ROWB + v * 32 + lane_off)
                                 : Vec16{0u, 0u, 0u, 0u};
         }
     }
@@ -283,9 +252,10 @@ static int launch_prefill_t(const PrefillArgs& a, int64_t pairs, hipStream_t str
 }
 
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
-                   const int32_t* cache_len, float* score, float* rows, hipStream_t stream)
+                   const int32_t* cache_len, float* score, float* rows, bool q_in_place, hipStream_t stream)
 {
     PrefillArgs a;
+    a.q_in_place = q_in_place ? 1 : 0;
     a.rows = rows;
     a.q_tail = static_cast<const char*>(q_tail);
     a.k_cache = static_cast<const char*>(k_cache);

@@ -499,6 +499,63 @@ def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
         assert torch.equal(a[3][s, :, :L], b_[3][s, :, :L])
 
 
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64)])
+def test_prefill_attention_matches_the_oracle(env, dtype, d):
+    # dense causal attention over the prompt (Eq. 1-2) on MFMA, plus the importance seed.
+    # Tolerance from the arithmetic: the weights are rounded once to the cache dtype before the
+    # second product (unit roundoff u = 2^-11 fp16, 2^-8 bf16), values are exact, sums are fp32,
+    # the output is rounded once: |delta_c| <= 1.5 u (sum_j p_j |v_jc| + |out_c|) + 1e-5.
+    O, B, W, LS = env
+    u = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    lens = [1, 31, 32, 33, 127, 128, 129, 300, 417]
+    wl = W.Workload(f"t_pf_{dtype}_{d}", 44, b=len(lens), h=2, d=d, dtype=dtype, prompt_lo=1, prompt_hi=417,
+                    steps=2, w=4, sparsity_bp=8000, hh_frac=0.02)
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    g = torch.Generator(device="cuda").manual_seed(77)
+    for s_i, L in enumerate(lens):           # fixed lengths that straddle the tile and block sizes
+        k = torch.randn((wl.h, L, d), generator=g, device="cuda")
+        v = torch.randn((wl.h, L, d), generator=g, device="cuda")
+        prompt["K"][s_i] = float("nan")
+        prompt["V"][s_i] = float("nan")
+        prompt["K"][s_i, :, :L] = k.to(wl.torch_dtype)
+        prompt["V"][s_i, :, :L] = v.to(wl.torch_dtype)
+    cache_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
+    Q = torch.full((wl.b, wl.h, wl.cap, d), float("nan"), dtype=wl.torch_dtype, device="cuda")
+    for s_i, L in enumerate(lens):
+        Q[s_i, :, :L] = (1.5 * torch.randn((wl.h, L, d), generator=g, device="cuda")).to(wl.torch_dtype)
+    out = torch.full_like(Q, 7.0)
+    R = 5
+    score = torch.full((wl.b, wl.h, wl.cap), float("nan"), dtype=torch.float32, device="cuda")
+    params = B.make_params(wl.b, wl.h, d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+    ws = torch.zeros((B.swa_workspace_bytes(params),), dtype=torch.uint8, device="cuda")
+    B.swa_prefill_attention(params, Q, prompt["K"], prompt["V"], cache_len, out, R, score, ws)
+    torch.cuda.synchronize()
+    Kn, Vn, Qn = (np.nan_to_num(x.double().cpu().numpy(), nan=0.0) for x in (prompt["K"], prompt["V"], Q))
+    ln = np.array(lens, dtype=np.int32)
+    ref = O.prefill_attention(Qn, Kn, Vn, ln, wl.scale)
+    mag = O.prefill_attention(Qn, Kn, np.abs(Vn), ln, wl.scale)
+    og = out.double().cpu().numpy()
+    for s_i, L in enumerate(lens):
+        assert np.all(og[s_i, :, L:] == 7.0), "rows past the prompt must not be written"
+        err = np.abs(og[s_i, :, :L] - ref[s_i, :, :L])
+        bound = 1.5 * u * (mag[s_i, :, :L] + np.abs(ref[s_i, :, :L])) + 1e-5
+        assert np.all(np.isfinite(og[s_i, :, :L]))
+        assert np.all(err <= bound), f"len {L}: max excess {np.max(err - bound):.3e}"
+    # the seed equals the seed routine fed with the last R query rows
+    q_tail = np.zeros((wl.b, wl.h, R, d))
+    for s_i, L in enumerate(lens):
+        for r in range(R):
+            if L - R + r >= 0:
+                q_tail[s_i, :, r] = Qn[s_i, :, L - R + r]
+    S_ref = O.prefill_scores(q_tail, Kn, ln, wl.scale)
+    S_g = score.double().cpu().numpy()
+    np.testing.assert_allclose(S_g, S_ref, rtol=1e-5, atol=1e-12)
+    # R = 0: attention only
+    out2 = torch.full_like(Q, 7.0)
+    B.swa_prefill_attention(params, Q, prompt["K"], prompt["V"], cache_len, out2, 0, None, ws)
+    assert torch.equal(out2, out)
+
+
 def test_prefill_scores_edge_shapes(env):
     O, B, W, LS = env
     for dtype, d in [("f16", 128), ("bf16", 64), ("f32", 128)]:
