@@ -288,6 +288,34 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     return res
 
 
+def bench_prefill_attention(wl, torch, B, W):
+    """swa_prefill_attention over the workload's prompts: time and MFMA rate (dense causal attention,
+    4 d flops per visible (query, key) pair) of the attention kernel, seed included in the time."""
+    prompt = W.make_prompt(wl, "cuda")
+    lens = prompt["lengths"]
+    g = torch.Generator(device="cuda").manual_seed(wl.seed)
+    Q = torch.randn((wl.b, wl.h, wl.cap, wl.d), generator=g, device="cuda", dtype=torch.float32).to(wl.torch_dtype)
+    out = torch.zeros_like(Q)
+    score = torch.zeros((wl.b, wl.h, wl.cap), dtype=torch.float32, device="cuda")
+    R = wl.prefill_R if wl.prefill_R > 0 else min(max(wl.w, 1), B.SWA_MAX_PREFILL_ROWS)
+    params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, len_bound=max(lens))
+    ws = torch.zeros((B.swa_workspace_bytes(params),), dtype=torch.uint8, device="cuda")
+    times = []
+    for it in range(3):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        B.swa_prefill_attention(params, Q, prompt["K"], prompt["V"], prompt["cache_len"], out, R, score, ws)
+        e1.record()
+        torch.cuda.synchronize()
+        times.append(e0.elapsed_time(e1))
+    ms = min(times[1:])
+    flops = sum(4.0 * wl.d * L * (L + 1) / 2 for L in lens) * wl.h
+    return {"ms": ms, "tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
+            "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "seed_rows": R,
+            "note": "dense causal attention over the prompts + importance seed, one call"}
+
+
 def cpu_baseline(wl, W, torch, budget_s=10.0):
     """The fp64 oracle, as it stands, timed on the host cores on a bounded sample."""
     import numpy as np
@@ -364,6 +392,8 @@ def main():
     ap.add_argument("--compact-every", type=int, default=1,
                     help="with --step-mode split: call swa_compact_kv only every C-th step (0 = never); between "
                          "compactions the cache keeps every token and the selection runs over all of them")
+    ap.add_argument("--prefill-attention", action="store_true",
+                    help="also time swa_prefill_attention over the workload's prompts (fp16/bf16 workloads)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -438,6 +468,8 @@ def main():
                                        "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
                                        "prefill_seed_ms", "quantize_kv_ms")},
     }
+    if args.prefill_attention and wl.dtype != "f32":
+        line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)
 

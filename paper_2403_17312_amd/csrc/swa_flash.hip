@@ -66,7 +66,12 @@ __global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
     static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
 
     __shared__ __align__(16) char s_k[2][BK * KSTR];
-    __shared__ __align__(16) char s_vt[2][D * VSTR];
+    // Channel c's row of the transposed value tile starts at vt_row(c): every group of 8 channels
+    // is skewed by another 16 bytes, so the 16 lanes that scatter one key's 128 channels (8 apart)
+    // hit 16 different banks.
+    constexpr int VT_BYTES = D * VSTR + (D / 8) * 16;
+    __shared__ __align__(16) char s_vt[2][VT_BYTES];
+    auto vt_row = [](int c) { return c * VSTR + (c >> 3) * 16; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -121,7 +126,7 @@ __global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
             const int posk = ((i16 / 8) * 2 + hbk) * 8 + (i16 % 8);
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<uint16_t*>(s_vt[buf] + (cc * 8 + e) * VSTR + posk * 2) = (uint16_t)half_of(gv[x], e);
+                *reinterpret_cast<uint16_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) = (uint16_t)half_of(gv[x], e);
         }
     };
 
@@ -145,15 +150,18 @@ __global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
             const char* kb = s_k[buf] + l32 * KSTR + hb * 16;
 #pragma unroll
             for (int v = 0; v < NV; ++v) c = Mfma<T>::run(load16(kb + v * 32), qv[v], c);   // C[key][query]
-            float z[16];
-            float mx = -INFINITY;
+            // only the tiles that reach the wave's diagonal need the causal mask
+            if (kt * BK + BK - 1 > w_lo) {
 #pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                const int key = kt * BK + 8 * (i / 4) + 4 * hb + (i % 4);
-                z[i] = (key <= tq) ? c[i] * a.scale_log2e : -INFINITY;
-                mx = fmaxf(mx, z[i]);
+                for (int i = 0; i < 16; ++i) {
+                    const int key = kt * BK + 8 * (i / 4) + 4 * hb + (i % 4);
+                    c[i] = (key <= tq) ? c[i] : -INFINITY;
+                }
             }
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+            float mx = c[0];
+#pragma unroll
+            for (int i = 1; i < 16; ++i) mx = fmaxf(mx, c[i]);
+            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * a.scale_log2e;     // scale > 0: max commutes
             // tile 0 holds key 0, visible to every query, so the running maximum is finite from
             // the first tile on
             const float m_new = fmaxf(m, mx);
@@ -162,19 +170,22 @@ __global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
             float ps = 0.f;
 #pragma unroll
             for (int i = 0; i < 16; ++i) {
-                p[i] = __builtin_amdgcn_exp2f(z[i] - m_new);           // 0 for masked keys
+                p[i] = __builtin_amdgcn_exp2f(__builtin_fmaf(c[i], a.scale_log2e, -m_new));   // 0 for masked keys
                 ps += p[i];
             }
             l = l * alpha + ps;
             m = m_new;
+            // the running maximum settles after a few tiles: rescale only when some query's moved
+            if (__any(alpha != 1.f)) {
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct)
+                for (int ct = 0; ct < CT; ++ct)
 #pragma unroll
-                for (int i = 0; i < 16; ++i) o[ct][i] *= alpha;
+                    for (int i = 0; i < 16; ++i) o[ct][i] *= alpha;
+            }
             const Vec16 p0 = pack<T>(p), p1 = pack<T>(p + 8);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
-                const char* vb = s_vt[buf] + (ct * 32 + l32) * VSTR + hb * 16;
+                const char* vb = s_vt[buf] + vt_row(ct * 32 + l32) + hb * 16;
                 o[ct] = Mfma<T>::run(load16(vb), p0, o[ct]);                                  // C[channel][query]
                 o[ct] = Mfma<T>::run(load16(vb + 32), p1, o[ct]);
             }
