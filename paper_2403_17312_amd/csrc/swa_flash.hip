@@ -26,8 +26,11 @@ struct FlashArgs {
     char* out;
     const int32_t* cache_len;
     int32_t h, cap;
+    int32_t pairs, nqb;    // (sequence, head) pairs and query blocks per pair in the grid
     float scale_log2e;
 };
+
+constexpr int kXcds = 8;   // workgroups are dealt round-robin to the 8 XCDs, each with its own L2
 
 // Half-precision element e (0..7) of a 16-byte vector, in the low 16 bits.
 __device__ __forceinline__ uint32_t half_of(const Vec16& v, int e)
@@ -78,10 +81,16 @@ __global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
     const int wave = tid >> 6;
     const int l32 = lane & 31;
     const int hb = lane >> 5;
-    const int64_t pair = blockIdx.x;
+    // XCD-aware placement: the query blocks of one pair all read the same K and V, so they go to
+    // the same XCD, next to each other in launch order, and share the pair's rows through that
+    // XCD's L2; the XCDs work on different pairs.  Longest blocks of a pair first.
+    const int xcd = blockIdx.x % kXcds;
+    const int idx = blockIdx.x / kXcds;
+    const int64_t pair = xcd + (int64_t)kXcds * (idx / a.nqb);
+    if (pair >= a.pairs) return;
     int s = a.cache_len[pair / a.h];
     s = s > a.cap ? a.cap : s;
-    const int qb = (int)gridDim.y - 1 - (int)blockIdx.y;   // longest blocks first
+    const int qb = a.nqb - 1 - idx % a.nqb;
     const int q0 = qb * BQ;
     if (q0 >= s) return;
 
@@ -225,7 +234,12 @@ int launch_flash_prefill(const swa_params& p, float scale, const void* q, const 
     a.cap = p.cap;
     a.scale_log2e = scale * 1.44269504088896340736f;
     const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
-    const dim3 grid((unsigned)((int64_t)p.b * p.h), (unsigned)((bound + 127) / 128));
+    a.pairs = p.b * p.h;
+    a.nqb = (bound + 127) / 128;
+    const int64_t per_xcd = ((int64_t)a.pairs + kXcds - 1) / kXcds;
+    const int64_t wgs = per_xcd * kXcds * a.nqb;
+    if (wgs > 0x7fffffffLL) return SWA_ERR_BAD_SHAPE;
+    const dim3 grid((unsigned)wgs);
     if (p.dtype == SWA_F16) {
         if (p.d == 64) hipLaunchKernelGGL((swa_flash_prefill_kernel<F16, 64>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((swa_flash_prefill_kernel<F16, 128>), grid, dim3(256), 0, stream, a);
