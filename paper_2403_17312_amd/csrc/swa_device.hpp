@@ -73,11 +73,19 @@ __device__ __forceinline__ uint32_t f2u(float f) { return __builtin_bit_cast(uin
 __device__ __forceinline__ float bf16_lo(uint32_t u) { return u2f(u << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t u) { return u2f(u & 0xffff0000u); }
 
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float float2_t __attribute__((ext_vector_type(2)));
+
+// Two fp32 values rounded to bf16 (nearest even) in one dword: v_cvt_pk_bf16_f32 on gfx950.
+__device__ __forceinline__ uint32_t f32x2_to_bf16x2_bits(float lo, float hi)
+{
+    const float2_t f = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(f, bf16x2_t));
+}
+
 __device__ __forceinline__ uint32_t f32_to_bf16_bits(float f)
 {
-    uint32_t u = f2u(f);
-    if ((u & 0x7fffffffu) > 0x7f800000u) return (u >> 16) | 0x40u;  // quiet NaN
-    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;                  // round to nearest even
+    return f32x2_to_bf16x2_bits(f, 0.f) & 0xffffu;
 }
 
 __device__ __forceinline__ uint32_t f32_to_f16_bits(float f)
@@ -271,10 +279,10 @@ template <>
 __device__ __forceinline__ Vec16 pack<BF16>(const float* f)
 {
     Vec16 v;
-    v.x = f32_to_bf16_bits(f[0]) | (f32_to_bf16_bits(f[1]) << 16);
-    v.y = f32_to_bf16_bits(f[2]) | (f32_to_bf16_bits(f[3]) << 16);
-    v.z = f32_to_bf16_bits(f[4]) | (f32_to_bf16_bits(f[5]) << 16);
-    v.w = f32_to_bf16_bits(f[6]) | (f32_to_bf16_bits(f[7]) << 16);
+    v.x = f32x2_to_bf16x2_bits(f[0], f[1]);
+    v.y = f32x2_to_bf16x2_bits(f[2], f[3]);
+    v.z = f32x2_to_bf16x2_bits(f[4], f[5]);
+    v.w = f32x2_to_bf16x2_bits(f[6], f[7]);
     return v;
 }
 

@@ -50,7 +50,7 @@ __device__ __forceinline__ uint32_t pack2<F16>(float f0, float f1)
 template <>
 __device__ __forceinline__ uint32_t pack2<BF16>(float f0, float f1)
 {
-    return f32_to_bf16_bits(f0) | (f32_to_bf16_bits(f1) << 16);
+    return f32x2_to_bf16x2_bits(f0, f1);
 }
 
 template <typename T, int D>
