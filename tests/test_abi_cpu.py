@@ -187,6 +187,24 @@ def test_strict_window_entry_points_validate_their_arguments(B):
     assert L.swa_prefill_rows(ctypes.byref(p0), ctypes.c_void_p(0x1004), 4, ok, ok, ok, ok, ok) == B.SWA_ERR_ALIGNMENT
 
 
+def test_prefill_attention_validates_its_arguments(B):
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    p16 = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_BF16)
+    p32 = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F32)
+
+    def call(p, q=ok, R=4, score=ok, out=ok):
+        return L.swa_prefill_attention(ctypes.byref(p), q, ok, ok, ok, out, R, score, ok, ok)
+    assert call(p32) == B.SWA_ERR_UNSUPPORTED_DTYPE              # 16-bit MFMA path only
+    assert call(p16, q=None) == B.SWA_ERR_NULL
+    assert call(p16, out=None) == B.SWA_ERR_NULL
+    assert call(p16, R=4, score=None) == B.SWA_ERR_NULL          # a seed needs somewhere to go
+    assert call(p16, R=-1) == B.SWA_ERR_BAD_SHAPE
+    assert call(p16, R=B.SWA_MAX_PREFILL_ROWS + 1) == B.SWA_ERR_BAD_SHAPE
+    assert call(p16, q=ctypes.c_void_p(0x1008)) == B.SWA_ERR_ALIGNMENT
+    assert L.swa_prefill_attention(None, ok, ok, ok, ok, ok, 4, ok, ok, ok) == B.SWA_ERR_NULL
+
+
 def test_binding_fails_loudly_without_the_library(B, monkeypatch, tmp_path):
     monkeypatch.setattr(B, "_lib", None)
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))

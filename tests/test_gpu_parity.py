@@ -284,6 +284,36 @@ def test_c4_opt30b_full_size_sampled_pairs_with_mfma_prefill(env):
     assert rep.steps == 128
 
 
+def test_full_size_sampled_pairs_in_the_other_step_forms(env):
+    # configs 3-5 at full size on the GPU, in the launch configurations bench.py times with
+    # --kv-int8, --step-mode window and --step-mode shared; sampled pairs checked
+    O, B, W, LS = env
+    c3, c4, c5 = W.CONFIGS["c3_opt13b"], W.CONFIGS["c4_opt30b"], W.CONFIGS["c5_llama7b_sp80"]
+    _say("c3, compressed cache")
+    rep = LS.run_lockstep(c3, seqs=[0, 17, 63], heads=[0, 20, 39], slack="zero", use_len_bound=True,
+                          fused=True, unordered=True, kv_int8=True)
+    _say(f"  {rep}")
+    assert rep.steps == 64
+    _say("c3, strict window (R = w = 32)")
+    rep = LS.run_lockstep_window(c3, 32, seqs=[0, 17, 63], heads=[0, 20, 39], slack="zero", use_len_bound=True)
+    _say(f"  {rep}")
+    assert rep.steps == 64
+    _say("c4, strict window (R = w = 64), first steps")
+    rep = LS.run_lockstep_window(c4, 64, steps=6, seqs=[0, 31], heads=[0, 55], slack="zero", use_len_bound=True)
+    _say(f"  {rep}")
+    _say("c3, head-shared (all heads of two sequences)")
+    rep = LS.run_lockstep(c3, steps=16, seqs=[5, 63], slack="zero", use_len_bound=True, fused=True,
+                          unordered=True, head_shared=True)
+    _say(f"  {rep}")
+    lens = W.prompt_lengths(c5).tolist()
+    seqs = sorted({int(np.argmin(lens)), int(np.argmax(lens)), 100})
+    _say(f"c5 (80 %), compressed cache, seqs {seqs}")
+    rep = LS.run_lockstep(c5, steps=24, seqs=seqs, heads=[0, 31], slack="zero", use_len_bound=True, fused=True,
+                          unordered=True, kv_int8=True)
+    _say(f"  {rep}")
+    torch.cuda.empty_cache()
+
+
 @pytest.mark.parametrize("name", ["c5_llama7b_sp50", "c5_llama7b_sp80", "c5_llama7b_sp90"])
 def test_c5_llama7b_full_size_sampled_pairs(env, name):
     O, B, W, LS = env
