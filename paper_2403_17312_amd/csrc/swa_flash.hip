@@ -53,8 +53,9 @@ __device__ __forceinline__ uint32_t pack2<BF16>(float f0, float f1)
     return f32x2_to_bf16x2_bits(f0, f1);
 }
 
+// Three workgroups per CU (one wave of each per SIMD): 168 registers per lane, 38 KB of LDS each.
 template <typename T, int D>
-__global__ void __launch_bounds__(256) swa_flash_prefill_kernel(FlashArgs a)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) swa_flash_prefill_kernel(FlashArgs a)
 {
     constexpr int NT = 256;
     constexpr int ROWB = D * 2;
