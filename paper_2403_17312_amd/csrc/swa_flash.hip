@@ -70,12 +70,13 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
     static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
 
     __shared__ __align__(16) char s_k[2][BK * KSTR];
-    // Channel c's row of the transposed value tile starts at vt_row(c): every group of 8 channels
-    // is skewed by another 16 bytes, so the 16 lanes that scatter one key's 128 channels (8 apart)
-    // hit 16 different banks.
-    constexpr int VT_BYTES = D * VSTR + (D / 8) * 16;
+    // Channel c's row of the transposed value tile starts at vt_row(c): 80 bytes per row keep the
+    // 16-byte fragment reads of 16 consecutive channels on disjoint banks, and every group of 16
+    // channels is skewed by another 16 bytes so that the transposing stores (16 lanes, channels 8
+    // apart) spread over the banks as well.
+    constexpr int VT_BYTES = D * VSTR + (D / 16) * 16;
     __shared__ __align__(16) char s_vt[2][VT_BYTES];
-    auto vt_row = [](int c) { return c * VSTR + (c >> 3) * 16; };
+    auto vt_row = [](int c) { return c * VSTR + (c >> 4) * 16; };
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
@@ -112,31 +113,51 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
     const int w_hi = (w_lo + 31 < s - 1) ? w_lo + 31 : s - 1;
     const int my_last = (w_lo < s) ? w_hi / BK : -1;      // last tile with a visible key for this wave
 
+    // Which tile rows a thread stages.  With two chunks per thread (d = 128) they are an even key
+    // and its successor, which sit next to each other in a lane's key order, so their values are
+    // stored to the transposed tile as one dword; the four (even key) slots of a wave are chosen
+    // so that, with the 16 channel groups, its 64 stores hit 64 different banks.
+    auto tile_key = [&](int x) {
+        if constexpr (LD == 2) {
+            const int q = tid / CPR;                 // 0..15
+            const int pr = (q & 1) + 4 * ((q >> 1) & 1) + 2 * ((q >> 2) & 1) + 8 * (q >> 3);
+            return 2 * pr + x;
+        } else {
+            return (tid + x * NT) / CPR;
+        }
+    };
     Vec16 gk[LD], gv[LD];
     auto gload = [&](int kt) {
 #pragma unroll
         for (int x = 0; x < LD; ++x) {
-            const int id = tid + x * NT;
-            const int j = id / CPR, cc = id % CPR;
+            const int j = tile_key(x), cc = tid % CPR;
             int row = kt * BK + j;
             row = row < s ? row : s - 1;          // rows past the prompt are masked; keep them finite
             gk[x] = load16(Kp + (int64_t)row * ROWB + cc * 16);
             gv[x] = load16(Vp + (int64_t)row * ROWB + cc * 16);
         }
     };
+    // key j is element i16 of half-wave hbk's 16 keys: its place (in halfs) in a channel's row
+    auto key_slot = [](int j) {
+        const int i16 = 4 * (j / 8) + (j % 4);
+        const int hbk = (j / 4) % 2;
+        return ((i16 / 8) * 2 + hbk) * 8 + (i16 % 8);
+    };
     auto lstore = [&](int buf) {
+        const int cc = tid % CPR;
 #pragma unroll
-        for (int x = 0; x < LD; ++x) {
-            const int id = tid + x * NT;
-            const int j = id / CPR, cc = id % CPR;
-            store16(s_k[buf] + j * KSTR + cc * 16, gk[x]);
-            // key j is element i16 of half-wave hbk's 16 keys: its place in the channel's row
-            const int i16 = 4 * (j / 8) + (j % 4);
-            const int hbk = (j / 4) % 2;
-            const int posk = ((i16 / 8) * 2 + hbk) * 8 + (i16 % 8);
+        for (int x = 0; x < LD; ++x) store16(s_k[buf] + tile_key(x) * KSTR + cc * 16, gk[x]);
+        if constexpr (LD == 2) {
+            const int posk = key_slot(tile_key(0));      // even, and key_slot(tile_key(1)) == posk + 1
 #pragma unroll
             for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<uint16_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) = (uint16_t)half_of(gv[x], e);
+                *reinterpret_cast<uint32_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) =
+                    half_of(gv[0], e) | (half_of(gv[1], e) << 16);
+        } else {
+            const int posk = key_slot(tile_key(0));
+#pragma unroll
+            for (int e = 0; e < 8; ++e)
+                *reinterpret_cast<uint16_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) = (uint16_t)half_of(gv[0], e);
         }
     };
 
