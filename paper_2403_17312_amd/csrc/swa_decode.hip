@@ -163,6 +163,26 @@ swa_decode_kernel(DecodeArgs a)
     const int64_t pair = blockIdx.x;
     const int s = (int)(pair / a.h);
 
+    // The first stage of the streaming pass is requested before the lengths are known (they are a
+    // dependent round trip of their own): its rows exist whatever the length is (clamped to the
+    // last slot), and whatever lies at or beyond `len` is replaced by the new row when the stage
+    // is reduced.  Volatile so that the loads stay up here; they are waited for at their first use.
+    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    Vec16 k0[UF], v0[UF];
+    if (a.phase != 2) {
+        const char* Kq = a.k_cache + pair * (int64_t)a.cap * ROWB;
+        const char* Vq = a.v_cache + pair * (int64_t)a.cap * ROWB;
+#pragma unroll
+        for (int u = 0; u < UF; ++u) {
+            int row = u * NG + grp;
+            row = row < a.cap ? row : a.cap - 1;
+            const u32x4_t kk = *reinterpret_cast<const volatile u32x4_t*>(Kq + (int64_t)row * ROWB + sub * 16);
+            const u32x4_t vv = *reinterpret_cast<const volatile u32x4_t*>(Vq + (int64_t)row * ROWB + sub * 16);
+            k0[u] = Vec16{kk[0], kk[1], kk[2], kk[3]};
+            v0[u] = Vec16{vv[0], vv[1], vv[2], vv[3]};
+        }
+    }
+
     const int len = a.cache_len[s];
     const int n = a.seq_len[s];
     const int m = len + 1;
@@ -334,7 +354,11 @@ swa_decode_kernel(DecodeArgs a)
                 }
             };
             Vec16 kA[UF], vA[UF], kB[UF], vB[UF];
-            load_stage(0, kA, vA);
+#pragma unroll
+            for (int u = 0; u < UF; ++u) {
+                kA[u] = k0[u];
+                vA[u] = v0[u];
+            }
             if (fc) new_row_ready();
             for (int base = 0; base < m; base += 2 * STEP) {
                 load_stage(base + STEP, kB, vB);
