@@ -167,9 +167,11 @@ swa_decode_kernel(DecodeArgs a)
     // dependent round trip of their own): its rows exist whatever the length is (clamped to the
     // last slot), and whatever lies at or beyond `len` is replaced by the new row when the stage
     // is reduced.  Volatile so that the loads stay up here; they are waited for at their first use.
+    // (Not for the 8-bit cache: its lanes have no registers to spare, and it measured slower.)
     typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+    constexpr bool kEarlyStage = !kQ8;
     Vec16 k0[UF], v0[UF];
-    if (a.phase != 2) {
+    if (kEarlyStage && a.phase != 2) {
         const char* Kq = a.k_cache + pair * (int64_t)a.cap * ROWB;
         const char* Vq = a.v_cache + pair * (int64_t)a.cap * ROWB;
 #pragma unroll
@@ -354,10 +356,14 @@ swa_decode_kernel(DecodeArgs a)
                 }
             };
             Vec16 kA[UF], vA[UF], kB[UF], vB[UF];
+            if constexpr (kEarlyStage) {
 #pragma unroll
-            for (int u = 0; u < UF; ++u) {
-                kA[u] = k0[u];
-                vA[u] = v0[u];
+                for (int u = 0; u < UF; ++u) {
+                    kA[u] = k0[u];
+                    vA[u] = v0[u];
+                }
+            } else {
+                load_stage(0, kA, vA);
             }
             if (fc) new_row_ready();
             for (int base = 0; base < m; base += 2 * STEP) {
