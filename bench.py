@@ -402,7 +402,7 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
-              "(the path shards over (sequence, head) pairs with no exchange, see DESIGN.md)",
+              "(the path shards over (sequence, head) pairs with no exchange between GPUs)",
               file=sys.stderr)
         sys.exit(2)
 

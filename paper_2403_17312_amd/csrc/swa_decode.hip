@@ -24,6 +24,18 @@
 // LDS radix select (4 x 8 bits, most significant first) finds the n_global-th
 // largest key, and an ordered ballot/popcount compaction writes the ascending
 // kept list with ties resolved towards the lowest slot.
+//
+// The same kernel also carries, selected by its arguments:
+//   * fused compaction (the kept rows move to slots 0..keep-1 inside the step), either in token
+//     order (rows behind a hole shift down, newest rows parked in LDS) or unordered (holes are
+//     filled by kept rows from above `keep`; window and tie rule then go by token position);
+//   * the head-reduced token set of Algorithm 1's header (phase 1 publishes every pair's new
+//     importance, weights and dense output; after a sum over the heads, phase 2 selects and
+//     finishes);
+//   * the 8-bit compressed cache of Section V-B (the Q8 instantiation: codes are converted and
+//     multiplied in registers, scale and zero point are folded into the query and the output);
+//   * the strict local attention sum (importance = sum of a ring of the last R attention rows,
+//     whose columns follow their tokens through the compaction).
 #include "swa_kernels.hpp"
 #ifndef SWA_UF
 #define SWA_UF 2
