@@ -111,11 +111,14 @@ __device__ __forceinline__ void merge_acc(float& M, float& S, float* acc, float 
 }
 
 // Register budget: five waves per SIMD (96 VGPRs) for the 16- and 32-bit caches, four (128) for
-// the 8-bit one, whose lanes carry 16 channels each; neither bound spills.
-template <typename T, int D, int NT>
+// the 8-bit one, whose lanes carry 16 channels each; neither bound spills.  RING: the strict
+// local attention sum, a separate instantiation so that the other forms carry none of its code.
+template <typename T, int D, int NT, bool RING>
 __global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(Elem<T>::kBytes == 1 ? 4 : 5)))
 swa_decode_kernel(DecodeArgs a)
 {
+    // a.ring is non-NULL exactly when RING (the launcher picks the instantiation)
+    const bool has_ring = RING;
     constexpr int EPV = Elem<T>::kPerVec;   // elements per 16-byte vector
     constexpr int LPR = D / EPV;            // lanes per row
     constexpr int NW = NT / kWave;
@@ -283,7 +286,7 @@ swa_decode_kernel(DecodeArgs a)
 #pragma unroll
         for (int k = 0; k < SPF; ++k) {
             const int i = tid + k * NT;
-            sold[k] = (i < len && !a.ring) ? Sp[i] : 0.f;
+            sold[k] = (i < len && !has_ring) ? Sp[i] : 0.f;
         }
         int32_t pold[SPF];
 #pragma unroll
@@ -431,6 +434,20 @@ swa_decode_kernel(DecodeArgs a)
         }
         __syncthreads();
 
+        // Strict window: request the ring entries of this thread's first slot now, so that they
+        // travel while the softmax runs (rings of up to kRingAhead rows; longer ones, and the
+        // further slots of long caches, are read in the accumulation loop itself).
+        constexpr int kRingAhead = 32;
+        float* Rg = has_ring ? a.ring + pair * (int64_t)a.ring_rows * cap : nullptr;
+        const bool ring_ahead = has_ring && a.ring_rows <= kRingAhead;
+        float rpre[kRingAhead];
+        if (ring_ahead) {
+            const bool old = tid < len;
+#pragma unroll
+            for (int j = 0; j < kRingAhead; ++j)
+                rpre[j] = (old && j < a.ring_rows && j != a.ring_row) ? Rg[(int64_t)j * cap + tid] : 0.f;
+        }
+
         // ---- softmax over the m cached slots ------------------------------------------
         mx = s_redA[0];
 #pragma unroll
@@ -450,7 +467,6 @@ swa_decode_kernel(DecodeArgs a)
 
         // Strict window: the rows of the ring in index order, the current weight standing in for
         // the row this step replaces; a token appended in this step has no earlier rows.
-        float* Rg = a.ring ? a.ring + pair * (int64_t)a.ring_rows * cap : nullptr;
         auto window_sum = [&](int i, float p) -> float {
             float t = 0.f;
             const bool old = i < len;
@@ -476,7 +492,15 @@ swa_decode_kernel(DecodeArgs a)
             if (i < m) {
                 const float p = s_p[i] / sum;
                 s_p[i] = p;
-                const float sc = a.ring ? window_sum(i, p) : sold[k] + p;
+                float sc;
+                if (ring_ahead && k == 0) {
+                    sc = 0.f;                         // same order of additions as window_sum
+#pragma unroll
+                    for (int j = 0; j < kRingAhead; ++j)
+                        if (j < a.ring_rows) sc += (j == a.ring_row) ? p : rpre[j];
+                } else {
+                    sc = has_ring ? window_sum(i, p) : sold[k] + p;
+                }
                 if (fc) {
                     s_sc[i] = sc;
                     s_pos[i] = pold[k];
@@ -502,7 +526,7 @@ swa_decode_kernel(DecodeArgs a)
         for (int i = tid + SPF * NT; i < m; i += NT) {
             const float p = s_p[i] / sum;
             s_p[i] = p;
-            const float sc = a.ring ? window_sum(i, p) : ((i == len) ? 0.f : Sp[i]) + p;
+            const float sc = has_ring ? window_sum(i, p) : ((i == len) ? 0.f : Sp[i]) + p;
             const int posi = (fc && i < len) ? Pp[i] : (n - 1);
             if (fc) {
                 s_sc[i] = sc;
@@ -891,9 +915,9 @@ swa_decode_kernel(DecodeArgs a)
                 src = src < 0 ? 0 : (src > len ? len : src);
                 Sp[j] = s_sc[src];
                 if (src != j || src == len) Pp[j] = s_pos[src];
-                if (a.ring) a.ring[(pair * a.ring_rows + a.ring_row) * (int64_t)cap + j] = s_p[src];
+                if (has_ring) a.ring[(pair * a.ring_rows + a.ring_row) * (int64_t)cap + j] = s_p[src];
             }
-            if (a.ring) {
+            if (has_ring) {
                 // The other rows of the ring follow the tokens that change slot (sources at or above
                 // `keep`, destinations below it: disjoint); the new token's column is zero there.
                 float* Rn = a.ring + pair * (int64_t)a.ring_rows * cap;
@@ -1049,10 +1073,10 @@ __global__ void __launch_bounds__(kHeadSumThreads) swa_headsum_kernel(const floa
     tot[(int64_t)s * cap + i] = t;
 }
 
-template <typename T, int D, int NT>
+template <typename T, int D, int NT, bool RING>
 static int launch_decode_nt(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, hipStream_t stream)
 {
-    auto kern = swa_decode_kernel<T, D, NT>;
+    auto kern = swa_decode_kernel<T, D, NT, RING>;
     int rc = ensure_dynamic_lds(reinterpret_cast<const void*>(kern), lds_bytes);
     if (rc != SWA_OK) return rc;
     hipLaunchKernelGGL(kern, dim3((unsigned)pairs), dim3(NT), lds_bytes, stream, a);
@@ -1062,10 +1086,19 @@ static int launch_decode_nt(const DecodeArgs& a, int64_t pairs, size_t lds_bytes
 template <typename T, int D>
 static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, int nt, hipStream_t stream)
 {
+    if constexpr (Elem<T>::kBytes != 1) {     // the strict window is not offered on the 8-bit cache
+        if (a.ring) {
+            switch (nt) {
+                case 128: return launch_decode_nt<T, D, 128, true>(a, pairs, lds_bytes, stream);
+                case 256: return launch_decode_nt<T, D, 256, true>(a, pairs, lds_bytes, stream);
+                default: return launch_decode_nt<T, D, 512, true>(a, pairs, lds_bytes, stream);
+            }
+        }
+    }
     switch (nt) {
-        case 128: return launch_decode_nt<T, D, 128>(a, pairs, lds_bytes, stream);
-        case 256: return launch_decode_nt<T, D, 256>(a, pairs, lds_bytes, stream);
-        default: return launch_decode_nt<T, D, 512>(a, pairs, lds_bytes, stream);
+        case 128: return launch_decode_nt<T, D, 128, false>(a, pairs, lds_bytes, stream);
+        case 256: return launch_decode_nt<T, D, 256, false>(a, pairs, lds_bytes, stream);
+        default: return launch_decode_nt<T, D, 512, false>(a, pairs, lds_bytes, stream);
     }
 }
 
