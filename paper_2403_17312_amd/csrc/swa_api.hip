@@ -100,6 +100,7 @@ static int validate(const swa_params* p)
     if ((p->flags & SWA_KV_INT8) && p->dtype != SWA_F16) return SWA_ERR_UNSUPPORTED_DTYPE;
     if ((p->flags & SWA_UNORDERED) && !(p->flags & SWA_FUSE_COMPACTION)) return SWA_ERR_BAD_SHAPE;
     if ((p->flags & SWA_HEAD_SHARED) && !(p->flags & SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
+    if ((p->flags & SWA_HEAD_SHARED) && p->b > 65535) return SWA_ERR_BAD_SHAPE;   // one grid row per sequence
     return SWA_OK;
 }
 
