@@ -499,6 +499,38 @@ def test_compressed_cache_and_strict_window_edge_cases(env):
             assert torch.equal(a[1][s], b_[1][s]) and torch.equal(a[2][s], b_[2][s]), mode
 
 
+def test_randomised_small_workloads_in_every_form(env):
+    # seeded sweep: random shapes, windows, budgets that change from step to step (so the number of
+    # evictions per step varies between none and most of the cache), every way of issuing the step
+    O, B, W, LS = env
+    rng = np.random.default_rng(20240317)
+    forms = ["split", "fused", "unordered", "shared", "q8", "q8_fused", "window", "lazy"]
+    for case in range(24):
+        form = forms[case % len(forms)]
+        d = int(rng.choice([64, 128]))
+        dtype = "f16" if form.startswith("q8") else str(rng.choice(["f32", "f16", "bf16"]))
+        hi = int(rng.integers(3, 420))
+        lo = int(rng.integers(1, hi + 1))
+        w = int(rng.choice([0, 1, 5, 17, B.SWA_W_EVEN_SPLIT]))
+        steps = int(rng.integers(6, 20))
+        sched = rng.integers(0, 9500, size=steps)
+        sched[rng.integers(0, steps)] = 0                       # at least one step that keeps everything
+        wl = W.Workload(f"t_rand_{case}", 50 + case, b=int(rng.integers(1, 4)), h=int(rng.integers(1, 5)), d=d,
+                        dtype=dtype, prompt_lo=lo, prompt_hi=hi, steps=steps, w=w, sparsity_bp=int(sched[0]),
+                        hh_frac=0.03, prefill_R=int(rng.choice([0, 0, 3, 9])))
+        _say(f"  case {case}: {form} {dtype} d={d} prompts {lo}..{hi} w={w} steps={steps}")
+        sp = lambda t, sched=sched: int(sched[t])
+        if form == "window":
+            LS.run_lockstep_window(wl.replace(prefill_R=0), int(rng.integers(1, 20)), sparsity_of_step=sp,
+                                   seed_rows=bool(rng.integers(0, 2)))
+        elif form == "lazy":
+            LS.run_lockstep(wl, compact_every=int(rng.integers(0, 5)), sparsity_of_step=sp)
+        else:
+            LS.run_lockstep(wl, fused=form in ("fused", "unordered", "shared", "q8_fused", "q8"),
+                            unordered=form in ("unordered", "shared", "q8"), head_shared=form == "shared",
+                            kv_int8=form.startswith("q8"), sparsity_of_step=sp)
+
+
 def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
     O, B, W, LS = env
     wl = W.Workload("t_det", 15, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=400,
