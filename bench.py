@@ -311,8 +311,9 @@ def bench_prefill_attention(wl, torch, B, W):
         times.append(e0.elapsed_time(e1))
     ms = min(times[1:])
     flops = sum(4.0 * wl.d * L * (L + 1) / 2 for L in lens) * wl.h
-    return {"ms": ms, "tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": 2500.0,
-            "frac": flops / (ms * 1e-3) / 1e12 / 2500.0, "seed_rows": R,
+    peak = 157.3 if wl.dtype == "f32" else 2500.0          # dense MFMA peak of the dtype, TFLOP/s
+    return {"ms": ms, "tflops": flops / (ms * 1e-3) / 1e12, "mfma_peak_tflops": peak,
+            "frac": flops / (ms * 1e-3) / 1e12 / peak, "seed_rows": R,
             "note": "dense causal attention over the prompts + importance seed, one call"}
 
 
@@ -393,7 +394,7 @@ def main():
                     help="with --step-mode split: call swa_compact_kv only every C-th step (0 = never); between "
                          "compactions the cache keeps every token and the selection runs over all of them")
     ap.add_argument("--prefill-attention", action="store_true",
-                    help="also time swa_prefill_attention over the workload's prompts (fp16/bf16 workloads)")
+                    help="also time swa_prefill_attention over the workload's prompts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -468,7 +469,7 @@ def main():
                                        "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
                                        "prefill_seed_ms", "quantize_kv_ms")},
     }
-    if args.prefill_attention and wl.dtype != "f32":
+    if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)

@@ -277,7 +277,7 @@ int swa_decode_step_window(const swa_params *params, const void *q, const void *
 
 /*
  * Prefill: dense causal attention over the whole prompt (Eq. 1-2 with the causal mask) plus the
- * importance seed of swa_prefill_scores, for fp16 and bf16.  For every pair and every prompt
+ * importance seed of swa_prefill_scores (every dtype; tuned for the 16-bit ones).  For every pair and every prompt
  * position t < cache_len[s]:
  *   out[t] = sum_{j<=t} softmax_{j<=t}(q[t] . K[j] * scale) V[j], rounded once to dtype;
  * if R > 0, score gets the column sums of the last R rows of that attention-weight matrix

@@ -237,7 +237,6 @@ int swa_prefill_attention(const swa_params* params, const void* q, const void* k
     if (rc != SWA_OK) return rc;
     (void)workspace;
     if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;
-    if (params->dtype != SWA_F16 && params->dtype != SWA_BF16) return SWA_ERR_UNSUPPORTED_DTYPE;
     if (!q || !k_cache || !v_cache || !cache_len || !out) return SWA_ERR_NULL;
     if (R < 0 || R > SWA_MAX_PREFILL_ROWS || (R > 0 && !score)) return R > 0 && !score ? SWA_ERR_NULL : SWA_ERR_BAD_SHAPE;
     if (!swa::aligned16(q) || !swa::aligned16(k_cache) || !swa::aligned16(v_cache) || !swa::aligned16(out))

@@ -53,29 +53,37 @@ __device__ __forceinline__ uint32_t pack2<BF16>(float f0, float f1)
     return f32x2_to_bf16x2_bits(f0, f1);
 }
 
-// Three workgroups per CU (one wave of each per SIMD): 168 registers per lane, 38 KB of LDS each.
+// 16-bit formats: three workgroups per CU (one wave of each per SIMD), 168 registers per lane,
+// 38 KB of LDS each.  fp32 (32x32x2 MFMA, four issues per 16-byte fragment) is there for
+// completeness, not speed: two waves per SIMD, and at d = 128 a single LDS buffer.
 template <typename T, int D>
-__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) swa_flash_prefill_kernel(FlashArgs a)
+__global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(Elem<T>::kBytes == 2 ? 3 : 2)))
+swa_flash_prefill_kernel(FlashArgs a)
 {
     constexpr int NT = 256;
-    constexpr int ROWB = D * 2;
-    constexpr int NV = D / 16;          // 16-byte vectors a lane supplies for a 32-row operand
+    constexpr int EB = Elem<T>::kBytes;     // 2 or 4
+    constexpr int EPV = Elem<T>::kPerVec;   // elements per 16-byte fragment: 8 or 4
+    constexpr int NP = 16 / EPV;            // fragments that hold a lane's 16 weights
+    constexpr int ROWB = D * EB;
+    constexpr int NV = ROWB / 32;       // 16-byte vectors a lane supplies for a 32-row operand
     constexpr int CT = D / 32;          // 32-channel tiles of the output
     constexpr int BK = 32;              // keys per tile
     constexpr int BQ = 128;             // queries per workgroup
     constexpr int KSTR = ROWB + 16;     // LDS row of the key tile, padded against bank conflicts
-    constexpr int VSTR = BK * 2 + 16;   // LDS row (one channel, 32 keys) of the transposed value tile
+    constexpr int VSTR = BK * EB + 16;  // LDS row (one channel, 32 keys) of the transposed value tile
     constexpr int CPR = ROWB / 16;      // 16-byte chunks per cache row
     constexpr int LD = BK * CPR / NT;   // chunks per thread, per tensor and tile
+    constexpr bool kPaired = EB == 2 && LD == 2;
+    constexpr int NBUF = (EB == 4 && D == 128) ? 1 : 2;   // LDS buffers (64 KB of static LDS at most)
     static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
 
-    __shared__ __align__(16) char s_k[2][BK * KSTR];
+    __shared__ __align__(16) char s_k[NBUF][BK * KSTR];
     // Channel c's row of the transposed value tile starts at vt_row(c): 80 bytes per row keep the
     // 16-byte fragment reads of 16 consecutive channels on disjoint banks, and every group of 16
     // channels is skewed by another 16 bytes so that the transposing stores (16 lanes, channels 8
     // apart) spread over the banks as well.
     constexpr int VT_BYTES = D * VSTR + (D / 16) * 16;
-    __shared__ __align__(16) char s_vt[2][VT_BYTES];
+    __shared__ __align__(16) char s_vt[NBUF][VT_BYTES];
     auto vt_row = [](int c) { return c * VSTR + (c >> 4) * 16; };
 
     const int tid = threadIdx.x;
@@ -118,7 +126,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
     // stored to the transposed tile as one dword; the four (even key) slots of a wave are chosen
     // so that, with the 16 channel groups, its 64 stores hit 64 different banks.
     auto tile_key = [&](int x) {
-        if constexpr (LD == 2) {
+        if constexpr (kPaired) {
             const int q = tid / CPR;                 // 0..15
             const int pr = (q & 1) + 4 * ((q >> 1) & 1) + 2 * ((q >> 2) & 1) + 8 * (q >> 3);
             return 2 * pr + x;
@@ -137,8 +145,11 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
             gv[x] = load16(Vp + (int64_t)row * ROWB + cc * 16);
         }
     };
-    // key j is element i16 of half-wave hbk's 16 keys: its place (in halfs) in a channel's row
+    // key j is element i16 of half-wave hbk's 16 keys: its place (in elements) in a channel's
+    // row.  16-bit: fragment v of half-wave hbk holds i16 = 8v..8v+7; fp32 fragments hold four
+    // consecutive keys, so there the natural order is already the lanes' order.
     auto key_slot = [](int j) {
+        if constexpr (EB == 4) return j;
         const int i16 = 4 * (j / 8) + (j % 4);
         const int hbk = (j / 4) % 2;
         return ((i16 / 8) * 2 + hbk) * 8 + (i16 % 8);
@@ -147,17 +158,29 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
         const int cc = tid % CPR;
 #pragma unroll
         for (int x = 0; x < LD; ++x) store16(s_k[buf] + tile_key(x) * KSTR + cc * 16, gk[x]);
-        if constexpr (LD == 2) {
+        if constexpr (kPaired) {
             const int posk = key_slot(tile_key(0));      // even, and key_slot(tile_key(1)) == posk + 1
 #pragma unroll
             for (int e = 0; e < 8; ++e)
                 *reinterpret_cast<uint32_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) =
                     half_of(gv[0], e) | (half_of(gv[1], e) << 16);
-        } else {
-            const int posk = key_slot(tile_key(0));
+        } else if constexpr (EB == 2) {
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
-                *reinterpret_cast<uint16_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) = (uint16_t)half_of(gv[0], e);
+            for (int x = 0; x < LD; ++x) {
+                const int posk = key_slot(tile_key(x));
+#pragma unroll
+                for (int e = 0; e < 8; ++e)
+                    *reinterpret_cast<uint16_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) = (uint16_t)half_of(gv[x], e);
+            }
+        } else {
+#pragma unroll
+            for (int x = 0; x < LD; ++x) {
+                const int posk = key_slot(tile_key(x));
+                const uint32_t w[4] = {gv[x].x, gv[x].y, gv[x].z, gv[x].w};
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    *reinterpret_cast<uint32_t*>(s_vt[buf] + vt_row(cc * 4 + e) + posk * 4) = w[e];
+            }
         }
     };
 
@@ -172,7 +195,7 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
     lstore(0);
     __syncthreads();
     for (int kt = 0; kt < nkt; ++kt) {
-        const int buf = kt & 1;
+        const int buf = kt % NBUF;
         if (kt + 1 < nkt) gload(kt + 1);
         if (kt <= my_last) {
             float16_t c;
@@ -213,15 +236,18 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
 #pragma unroll
                     for (int i = 0; i < 16; ++i) o[ct][i] *= alpha;
             }
-            const Vec16 p0 = pack<T>(p), p1 = pack<T>(p + 8);
+            Vec16 pv[NP];
+#pragma unroll
+            for (int v = 0; v < NP; ++v) pv[v] = pack<T>(p + v * EPV);
 #pragma unroll
             for (int ct = 0; ct < CT; ++ct) {
                 const char* vb = s_vt[buf] + vt_row(ct * 32 + l32) + hb * 16;
-                o[ct] = Mfma<T>::run(load16(vb), p0, o[ct]);                                  // C[channel][query]
-                o[ct] = Mfma<T>::run(load16(vb + 32), p1, o[ct]);
+#pragma unroll
+                for (int v = 0; v < NP; ++v) o[ct] = Mfma<T>::run(load16(vb + v * 32), pv[v], o[ct]);   // C[channel][query]
             }
         }
-        if (kt + 1 < nkt) lstore(buf ^ 1);
+        if constexpr (NBUF == 1) __syncthreads();      // every wave is done with the only buffer
+        if (kt + 1 < nkt) lstore((kt + 1) % NBUF);
         __syncthreads();
     }
 
@@ -233,11 +259,19 @@ __global__ void __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3))) s
 #pragma unroll
             for (int g = 0; g < 4; ++g) {
                 // channels 32 ct + 8 g + 4 hb + 0..3 of query t
-                uint32_t w[2];
+                char* dst = Op + (int64_t)t * ROWB + (32 * ct + 8 * g + 4 * hb) * EB;
+                if constexpr (EB == 4) {
+                    float f[4];
 #pragma unroll
-                for (int r = 0; r < 2; ++r)
-                    w[r] = pack2<T>(o[ct][4 * g + 2 * r] * inv, o[ct][4 * g + 2 * r + 1] * inv);
-                *reinterpret_cast<uint2*>(Op + (int64_t)t * ROWB + (32 * ct + 8 * g + 4 * hb) * 2) = make_uint2(w[0], w[1]);
+                    for (int r = 0; r < 4; ++r) f[r] = o[ct][4 * g + r] * inv;
+                    store16(dst, pack<F32>(f));
+                } else {
+                    uint32_t w[2];
+#pragma unroll
+                    for (int r = 0; r < 2; ++r)
+                        w[r] = pack2<T>(o[ct][4 * g + 2 * r] * inv, o[ct][4 * g + 2 * r + 1] * inv);
+                    *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+                }
             }
         }
     }
@@ -269,7 +303,8 @@ int launch_flash_prefill(const swa_params& p, float scale, const void* q, const 
         if (p.d == 64) hipLaunchKernelGGL((swa_flash_prefill_kernel<BF16, 64>), grid, dim3(256), 0, stream, a);
         else hipLaunchKernelGGL((swa_flash_prefill_kernel<BF16, 128>), grid, dim3(256), 0, stream, a);
     } else {
-        return SWA_ERR_UNSUPPORTED_DTYPE;
+        if (p.d == 64) hipLaunchKernelGGL((swa_flash_prefill_kernel<F32, 64>), grid, dim3(256), 0, stream, a);
+        else hipLaunchKernelGGL((swa_flash_prefill_kernel<F32, 128>), grid, dim3(256), 0, stream, a);
     }
     return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
 }

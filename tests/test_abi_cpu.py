@@ -195,7 +195,9 @@ def test_prefill_attention_validates_its_arguments(B):
 
     def call(p, q=ok, R=4, score=ok, out=ok):
         return L.swa_prefill_attention(ctypes.byref(p), q, ok, ok, ok, out, R, score, ok, ok)
-    assert call(p32) == B.SWA_ERR_UNSUPPORTED_DTYPE              # 16-bit MFMA path only
+    pq = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=B.SWA_KV_INT8)
+    assert call(pq) == B.SWA_ERR_UNSUPPORTED_DTYPE               # the prompt's cache is not compressed yet
+    assert call(p32, q=None) == B.SWA_ERR_NULL
     assert call(p16, q=None) == B.SWA_ERR_NULL
     assert call(p16, out=None) == B.SWA_ERR_NULL
     assert call(p16, R=4, score=None) == B.SWA_ERR_NULL          # a seed needs somewhere to go

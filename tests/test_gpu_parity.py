@@ -561,14 +561,17 @@ def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
         assert torch.equal(a[3][s, :, :L], b_[3][s, :, :L])
 
 
-@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64)])
+@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64), ("f32", 128),
+                                     ("f32", 64)])
 def test_prefill_attention_matches_the_oracle(env, dtype, d):
     # dense causal attention over the prompt (Eq. 1-2) on MFMA, plus the importance seed.
     # Tolerance from the arithmetic: the weights are rounded once to the cache dtype before the
     # second product (unit roundoff u = 2^-11 fp16, 2^-8 bf16), values are exact, sums are fp32,
     # the output is rounded once: |delta_c| <= 1.5 u (sum_j p_j |v_jc| + |out_c|) + 1e-5.
+    # (fp32: nothing is rounded below fp32; u = 2^-20 covers the fp32 sums over up to 417 keys and
+    # the hardware exponential.)
     O, B, W, LS = env
-    u = 2.0 ** -11 if dtype == "f16" else 2.0 ** -8
+    u = {"f16": 2.0 ** -11, "bf16": 2.0 ** -8, "f32": 2.0 ** -20}[dtype]
     lens = [1, 31, 32, 33, 127, 128, 129, 300, 417]
     wl = W.Workload(f"t_pf_{dtype}_{d}", 44, b=len(lens), h=2, d=d, dtype=dtype, prompt_lo=1, prompt_hi=417,
                     steps=2, w=4, sparsity_bp=8000, hh_frac=0.02)
