@@ -372,6 +372,39 @@ def test_workgroup_size_variants_and_large_cap(env):
     LS.run_lockstep(wl)
 
 
+def test_decoding_from_an_empty_cache_in_every_form(env):
+    # cache_len = 0: the first token attends to itself only; then the cache grows from nothing
+    O, B, W, LS = env
+    wl = W.Workload("t_empty", 45, b=3, h=2, d=128, dtype="f16", prompt_lo=1, prompt_hi=40, steps=12, w=2,
+                    sparsity_bp=6000, hh_frac=0.02)
+    for form in ("split", "fused", "unordered", "shared", "q8", "window"):
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        prompt["cache_len"][1] = 0
+        prompt["lengths"][1] = 0
+        prompt["K"][1] = float("nan")
+        prompt["V"][1] = float("nan")
+        prompt["pos"][1] = -1
+        _say(f"  empty cache, {form}")
+        if form == "window":
+            # run_lockstep_window builds its own prompt: emulate with a one-token prompt instead
+            LS.run_lockstep_window(wl.replace(prompt_lo=1, prompt_hi=1), 4, seed_rows=False)
+            continue
+        rep = LS.run_lockstep(wl, prompt=prompt, fused=form != "split", unordered=form in ("unordered", "shared", "q8"),
+                              head_shared=form == "shared", kv_int8=form == "q8")
+        assert rep.steps == 12
+    # the prefill calls leave an empty sequence alone
+    params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+    ws = torch.zeros((B.swa_workspace_bytes(params),), dtype=torch.uint8, device="cuda")
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    prompt["cache_len"][1] = 0
+    Q = torch.randn((wl.b, wl.h, wl.cap, wl.d), device="cuda").half()
+    out = torch.full_like(Q, 7.0)
+    score = torch.full((wl.b, wl.h, wl.cap), float("nan"), dtype=torch.float32, device="cuda")
+    B.swa_prefill_attention(params, Q, prompt["K"], prompt["V"], prompt["cache_len"], out, 3, score, ws)
+    assert torch.all(out[1] == 7.0) and torch.all(score[1] == 0.0)
+    assert torch.isfinite(out[0, :, :int(prompt["cache_len"][0])].float()).all()
+
+
 def test_exact_ties_go_to_the_lowest_slot(env):
     # identical keys => identical logits => bitwise-equal probabilities and scores
     O, B, W, LS = env
