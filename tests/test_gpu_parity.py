@@ -564,6 +564,93 @@ def test_randomised_small_workloads_in_every_form(env):
                             kv_int8=form.startswith("q8"), sparsity_of_step=sp)
 
 
+@pytest.mark.parametrize("form", ["unordered", "fused", "shared", "q8", "window"])
+def test_hip_graph_replays_equal_the_eager_run(env, form):
+    # bench.py times HIP-graph replays: a captured trajectory, replayed several times with the
+    # state restored eagerly in between, must give the eager run's bits every time
+    O, B, W, LS = env
+    wl = W.Workload("t_graph", 46, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=300, steps=8, w=8,
+                    sparsity_bp=8000, hh_frac=0.02)
+    flags = {"unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED, "fused": B.SWA_FUSE_COMPACTION,
+             "shared": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED,
+             "q8": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED, "window": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED}[form]
+    R = 8
+    prompt = W.make_prompt(wl, "cuda")
+    inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(wl.steps)]
+    seq_lens = [(prompt["cache_len"] + (t + 1)).to(torch.int32) for t in range(wl.steps)]
+    params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, flags=flags)
+    st = B.DecodeState(params, debug_probs=False)
+    ring = torch.zeros((wl.b, wl.h, R, wl.cap), device="cuda")
+    if form == "q8":
+        st.K.copy_(prompt["K"])
+        st.V.copy_(prompt["V"])
+        st.cache_len.copy_(prompt["cache_len"])
+        st.quantize()
+        prompt = dict(prompt, K=st.K.clone(), V=st.V.clone())
+    names = ["K", "V", "score", "pos", "cache_len", "kept_cnt"]
+
+    def reset():
+        st.K.copy_(prompt["K"])
+        st.V.copy_(prompt["V"])
+        st.pos.copy_(prompt["pos"])
+        st.score.zero_()
+        ring.zero_()
+        lens["a"].copy_(prompt["cache_len"])
+        lens["b"].zero_()
+
+    lens = {"a": st.cache_len, "b": st.kept_cnt}
+    outs = torch.zeros((wl.steps, wl.b, wl.h, wl.d), dtype=torch.float16, device="cuda")
+
+    def trajectory():
+        cur, nxt = lens["a"], lens["b"]
+        for t in range(wl.steps):
+            q, kn, vn = inputs[t]
+            if form == "window":
+                B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, R, t % R, st.score, st.pos, cur,
+                                         seq_lens[t], None, nxt, st.out, None, st.workspace)
+            elif form == "q8":
+                B.swa_decode_step_q8(st.params, q, kn, vn, st.K, st.V, st.qparams, st.score, st.pos, cur,
+                                     seq_lens[t], None, nxt, st.out, None, st.workspace)
+            else:
+                B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, cur, seq_lens[t], None, nxt,
+                                  st.out, None, st.workspace)
+            outs[t].copy_(st.out)
+            cur, nxt = nxt, cur
+        return cur                                    # the tensor that holds the final lengths
+
+    def snapshot(final_len):
+        L = final_len.tolist()
+        return (outs.clone(), [st.K[s, :, :L[s]].clone() for s in range(wl.b)],
+                [st.score[s, :, :L[s]].clone() for s in range(wl.b)],
+                [st.pos[s, :, :L[s]].clone() for s in range(wl.b)], L,
+                [ring[s, :, :, :L[s]].clone() for s in range(wl.b)])
+
+    reset()
+    final = trajectory()                              # eager reference (also warms every kernel up)
+    torch.cuda.synchronize()
+    ref = snapshot(final)
+    assert all(0 < x < wl.cap for x in ref[4]) and not torch.isnan(ref[0].float()).any()
+    reset()
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        final_g = trajectory()
+    assert final_g is final
+    for rep in range(3):
+        reset()
+        outs.zero_()
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        got = snapshot(final)
+        assert torch.equal(got[0], ref[0]), f"{form}: outputs of replay {rep}"
+        assert got[4] == ref[4]
+        for k in (1, 2, 3, 5):
+            for s_i in range(wl.b):
+                assert torch.equal(got[k][s_i], ref[k][s_i]), f"{form}: state {k} of replay {rep}"
+    assert st.check_status() == 0
+
+
 def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
     O, B, W, LS = env
     wl = W.Workload("t_det", 15, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=400,
