@@ -317,6 +317,24 @@ def bench_prefill_attention(wl, torch, B, W):
             "note": "dense causal attention over the prompts + importance seed, one call"}
 
 
+def stream_read_ceiling(torch, B):
+    """Streaming-read rate of this GPU on a 4 GiB buffer (plain 128-bit loads, nothing else)."""
+    x = torch.ones((1 << 30,), dtype=torch.float32, device="cuda")
+    sink = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    best = None
+    for _ in range(4):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.swa_probe_stream_read(x, x.numel() * 4, sink)
+        e1.record()
+        torch.cuda.synchronize()
+        ms = e0.elapsed_time(e1)
+        best = ms if best is None else min(best, ms)
+    del x
+    torch.cuda.empty_cache()
+    return (1 << 32) / (best * 1e-3) / 1e9
+
+
 def cpu_baseline(wl, W, torch, budget_s=10.0):
     """The fp64 oracle, as it stands, timed on the host cores on a bounded sample."""
     import numpy as np
@@ -469,6 +487,17 @@ def main():
                                        "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
                                        "prefill_seed_ms", "quantize_kv_ms")},
     }
+    ceil_gbs = stream_read_ceiling(torch, B)
+    line["roofline"]["measured_stream_read_gbs"] = ceil_gbs
+    line["roofline"]["frac_of_measured_stream_read"] = achieved / ceil_gbs
+    line["pair_rows_per_s"] = res["kv_tokens_per_s"] * wl.h
+    if res["prefill_seed_ms"]:
+        # one read of the prompt's keys and 2 R s d flops per pair per pass (two passes run)
+        lens = W.prompt_lengths(wl).tolist()
+        kb = sum(lens) * wl.h * wl.d * wl.elem_bytes
+        fl = 2.0 * 2.0 * wl.prefill_R * sum(lens) * wl.h * wl.d
+        line["detail"]["prefill_seed_gbs"] = kb / (res["prefill_seed_ms"] * 1e-3) / 1e9
+        line["detail"]["prefill_seed_tflops"] = fl / (res["prefill_seed_ms"] * 1e-3) / 1e12
     if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
     if not args.no_cpu_baseline:

@@ -291,6 +291,14 @@ int swa_prefill_attention(const swa_params *params, const void *q, const void *k
                           const void *v_cache, const int32_t *cache_len, void *out, int32_t R,
                           float *score, void *workspace, void *stream);
 
+/*
+ * Measurement aid, not part of the method: reads `bytes` (rounded down to a multiple of 104 KiB)
+ * from src with plain streaming 128-bit loads and discards them.  Timing it on a buffer much larger
+ * than the caches gives the streaming-read ceiling of the machine, the practical denominator next
+ * to the nominal HBM peak.  src: device pointer, 16-byte aligned; sink: 4 bytes of device memory.
+ */
+int swa_probe_stream_read(const void *src, size_t bytes, void *sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

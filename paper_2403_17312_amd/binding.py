@@ -34,7 +34,7 @@ SWA_MAX_WINDOW_ROWS = 64
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
-           "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention"]
+           "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read"]
 
 
 class SwaParams(ctypes.Structure):
@@ -90,6 +90,8 @@ def lib():
         L.swa_decode_step_window.argtypes = [pp] + [vp] * 6 + [ctypes.c_int32] * 2 + [vp] * 10
         L.swa_prefill_attention.restype = ctypes.c_int
         L.swa_prefill_attention.argtypes = [pp, vp, vp, vp, i32p, vp, ctypes.c_int32, vp, vp, vp]
+        L.swa_probe_stream_read.restype = ctypes.c_int
+        L.swa_probe_stream_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
         _lib = L
     return _lib
 
@@ -202,6 +204,11 @@ def swa_prefill_attention(params: SwaParams, q, k_cache, v_cache, cache_len, out
     _check(lib().swa_prefill_attention(ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(cache_len), _ptr(out), int(R), _ptr(score),
                                        _ptr(workspace), _stream(stream)), "swa_prefill_attention")
+
+
+def swa_probe_stream_read(src, nbytes: int, sink, stream=None) -> None:
+    _check(lib().swa_probe_stream_read(_ptr(src), int(nbytes), _ptr(sink), _stream(stream)),
+           "swa_probe_stream_read")
 
 
 def swa_compact_kv(params: SwaParams, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,

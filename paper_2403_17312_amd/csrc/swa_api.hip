@@ -85,6 +85,26 @@ int launch_workspace_init(const swa_params& p, void* workspace, hipStream_t stre
     return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
 }
 
+// Measurement aid: every workgroup streams its own contiguous piece of the buffer with 128-bit
+// loads, eight in flight per lane, and folds what it read into one word that is (almost) never
+// stored.  What this reaches is the streaming-read ceiling the decode kernel is compared with.
+__global__ void __launch_bounds__(256) swa_stream_read_kernel(const Vec16* src, size_t vec_per_block, uint32_t* sink)
+{
+    const Vec16* base = src + (size_t)blockIdx.x * vec_per_block;
+    uint32_t acc = 0;
+    for (size_t i = threadIdx.x; i < vec_per_block; i += (size_t)256 * 8) {
+        Vec16 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+            const size_t j = i + (size_t)u * 256;
+            v[u] = (j < vec_per_block) ? base[j] : Vec16{0u, 0u, 0u, 0u};
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;
+    }
+    if (acc == 0x9e3779b9u) sink[0] = acc;
+}
+
 static int validate(const swa_params* p)
 {
     if (!p) return SWA_ERR_NULL;
@@ -284,6 +304,19 @@ int swa_decode_step_q8(const swa_params* params, const void* q, const void* k_ne
     if (!qparams) return SWA_ERR_NULL;
     return decode_common(params, q, k_new, v_new, k_codes, v_codes, qparams, score, pos, cache_len, seq_len,
                          kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+int swa_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream)
+{
+    if (!src || !sink) return SWA_ERR_NULL;
+    if (!swa::aligned16(src)) return SWA_ERR_ALIGNMENT;
+    const size_t piece = 104 * 1024;                    // bytes per workgroup
+    const size_t blocks = bytes / piece;
+    if (blocks == 0 || blocks > 0x7fffffffULL) return SWA_ERR_BAD_SHAPE;
+    hipLaunchKernelGGL(swa::swa_stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0,
+                       static_cast<hipStream_t>(stream), static_cast<const swa::Vec16*>(src), piece / 16,
+                       static_cast<uint32_t*>(sink));
+    return hipGetLastError() == hipSuccess ? SWA_OK : SWA_ERR_HIP;
 }
 
 int swa_quantize_kv(const swa_params* params, const void* k_cache, const void* v_cache,
