@@ -19,7 +19,7 @@
  *     is full) never writes out of bounds: the affected pairs are skipped and a
  *     sticky bit is set in the workspace, readable with swa_check_status().
  *   - Tensors are dense, row-major:
- *       k_cache, v_cache  [b, h, cap, d]   element type params->dtype
+ *       k_cache, v_cache  [b, h, cap, d]   element type params->dtype (8-bit codes with SWA_KV_INT8)
  *       score             [b, h, cap]      float32 running importance
  *       pos               [b, h, cap]      int32 original token position
  *       kept_idx          [b, h, cap]      int32 ascending slot list
@@ -49,7 +49,7 @@ typedef enum {
     SWA_ERR_NULL = -1,              /* a required pointer is NULL */
     SWA_ERR_BAD_SHAPE = -2,         /* b, h, cap, w or R out of range */
     SWA_ERR_UNSUPPORTED_D = -3,     /* d not in {64, 128} */
-    SWA_ERR_UNSUPPORTED_DTYPE = -4, /* dtype not a swa_dtype */
+    SWA_ERR_UNSUPPORTED_DTYPE = -4, /* dtype not a swa_dtype, or a cache format the call does not take */
     SWA_ERR_BAD_SPARSITY = -5,      /* sparsity_bp outside 0..9999 */
     SWA_ERR_CAPACITY = -6,          /* cap above SWA_MAX_CAP, or (status) a cache was full */
     SWA_ERR_HIP = -7,               /* a HIP runtime call failed */
