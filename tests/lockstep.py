@@ -465,3 +465,58 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
         rep.steps += 1
     assert st.check_status() == 0
     return rep
+
+
+def run_free(wl: W.Workload, device="cuda", steps: Optional[int] = None):
+    """Free-running comparison (no state adoption): the GPU and the fp64 oracle each follow their
+    own trajectory from the same prompt.  While the kept sets agree, weights, importance and outputs
+    must agree within the usual tolerances.  At the first step where they differ, every token of
+    the symmetric difference must be a near tie in the oracle's own importance (within 2e-5
+    relative of the cutoff): that is the only way an fp32 path may part from the fp64 one.
+    Returns (first divergent step or None, flipped tokens at that step)."""
+    steps = wl.steps if steps is None else steps
+    prompt = W.make_prompt(wl, device, slack="nan")
+    st = new_state(wl, prompt)
+    K_o, V_o = np.nan_to_num(_np64(st.K)), np.nan_to_num(_np64(st.V))
+    pos_o = st.pos.cpu().numpy().copy()
+    len_o = st.cache_len.cpu().numpy().copy()
+    n_o = len_o.copy()
+    if wl.prefill_R > 0:
+        q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R)
+        st.prefill_scores(q_tail)
+        score_o = O.prefill_scores(_np64(q_tail), K_o, len_o, wl.scale)
+    else:
+        st.score.zero_()
+        score_o = np.zeros(K_o.shape[:3])
+    for t in range(steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        n_o = n_o + 1
+        st.decode_step(q, kn, vn)
+        kept_o, cnt_o, out_o, p_o = O.decode_step(_np64(q), _np64(kn), _np64(vn), K_o, V_o, score_o, pos_o, len_o,
+                                                  n_o, wl.w, wl.sparsity_bp, wl.scale)
+        kept_g = st.kept_idx.cpu().numpy()
+        cnt_g = st.kept_cnt.cpu().numpy()
+        assert np.array_equal(cnt_g, cnt_o)
+        p_g, s_g = _np64(st.probs), _np64(st.score)
+        for i, m in enumerate(len_o):
+            assert np.all(np.abs(p_g[i, :, :m] - p_o[i, :, :m]) <= 1e-5 * p_o[i, :, :m] + 1e-12), f"step {t}: probs"
+            assert np.all(np.abs(s_g[i, :, :m] - score_o[i, :, :m]) <= 1e-5 * score_o[i, :, :m] + 1e-12), f"step {t}: score"
+        flipped = 0
+        for i, c in enumerate(cnt_g):
+            m = len_o[i]
+            nl = O.budget(int(n_o[i]), int(m), wl.w, wl.sparsity_bp)[1]
+            for hd in range(wl.h):
+                diff = set(kept_g[i, hd, :c].tolist()) ^ set(kept_o[i, hd, :c].tolist())
+                if diff:
+                    cutoff = np.sort(score_o[i, hd, :m - nl])[::-1][c - nl - 1]
+                    for j in diff:
+                        assert abs(score_o[i, hd, j] - cutoff) <= 2e-5 * abs(cutoff), \
+                            f"step {t}: the paths part at token {j}, which is not a near tie"
+                    flipped += len(diff) // 2
+        if flipped:
+            return t, flipped
+        check_out(_np64(st.out), out_o, wl.dtype, f"free-running step {t} out")
+        st.compact()
+        O.compact(K_o, V_o, score_o, pos_o, kept_o, cnt_o, len_o)
+    return None, 0

@@ -42,6 +42,17 @@ def test_c1_tiny_with_prefill_seed_fp32_mfma(env):
     _say(f"  {rep}")
 
 
+def test_free_running_trajectories_part_only_at_near_ties(env):
+    # no state adoption: the fp32 GPU path and the fp64 oracle each run on their own; they may only
+    # part where the oracle's importance values are tied to within 2e-5 relative
+    O, B, W, LS = env
+    for name in ("c1_tiny", "c2_opt6p7b"):
+        step, flipped = LS.run_free(W.CONFIGS[name])
+        _say(f"  {name}: free-running, first divergent step {step} ({flipped} near-tie flips)")
+    step, flipped = LS.run_free(W.CONFIGS["c1_tiny"].replace(prefill_R=8))
+    _say(f"  c1_tiny with prefill seed: first divergent step {step} ({flipped} near-tie flips)")
+
+
 def test_c1_tiny_without_compaction(env):
     # decode steps back to back with no compaction: every slot stays a candidate
     O, B, W, LS = env
