@@ -8,11 +8,15 @@
  *
  * Conventions that hold for every entry point unless stated otherwise
  *   - `swa_params*` is a HOST pointer; every other pointer is a DEVICE pointer
- *     owned by the caller.  The library never allocates or frees device memory
- *     and keeps no global state.
+ *     owned by the caller.  The library never allocates or frees device memory.
+ *     The state it keeps per process is small and internal: which kernels have had
+ *     their LDS limit raised.  Everything a call computes goes through its arguments.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work: they never synchronise and never read device memory on
- *     the host, so a sequence of calls can be captured into a HIP graph.
+ *     the host, so a sequence of calls can be captured into a HIP graph.  A decode
+ *     launch that needs more than 48 KiB of LDS first raises the kernel's limit
+ *     (a host-side runtime call, once per kernel); call swa_prepare() once per
+ *     device beforehand and no call made during a capture does anything but launch.
  *   - Return value: SWA_OK (0) or a negative swa_status.  Errors that the host
  *     can see (null pointers, unsupported shapes) are reported before anything
  *     is enqueued.  A condition only the device can see (a sequence whose cache
@@ -103,6 +107,11 @@ typedef struct {
  *   - kept_idx[j], when given, is the PRE-compaction slot of the token that ends in slot j.
  * pos must hold each slot's token position (it does after any sequence of calls that started
  * from a cache filled in token order with pos = 0..len-1).  Up to 7168 live slots.
+ * The window rule assumes that the most recent min(w, m) tokens are all still cached, which holds
+ * as long as the effective window grows by at most one token per step (always true for a fixed
+ * w, and for SWA_W_EVEN_SPLIT at a fixed sparsity).  A caller that widens w, or lowers the
+ * sparsity under SWA_W_EVEN_SPLIT, by more than that between two calls must use the ordered form
+ * for that step: here the cache would then keep fewer than `keep` distinct live tokens.
  */
 #define SWA_UNORDERED 2
 #define SWA_MAX_UNORDERED_SLOTS 7168
@@ -125,6 +134,13 @@ typedef struct {
  * swa_decode_step_q8 and for swa_compact_kv on such a cache; swa_decode_step refuses it.
  */
 #define SWA_KV_INT8 8
+
+/*
+ * One-time set-up on the current device, optional but needed before stream capture: raises the
+ * LDS limit of every decode kernel to the device's maximum.  Host-side only; enqueues nothing.  Call it again after hipSetDevice
+ * to another GPU.
+ */
+int swa_prepare(void);
 
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);

@@ -34,7 +34,8 @@ SWA_MAX_WINDOW_ROWS = 64
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
-           "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read"]
+           "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read",
+           "swa_prepare"]
 
 
 class SwaParams(ctypes.Structure):
@@ -78,6 +79,8 @@ def lib():
         L.swa_prefill_scores.argtypes = [pp, vp, ctypes.c_int32, vp, i32p, vp, vp, vp]
         L.swa_decode_step.restype = ctypes.c_int
         L.swa_decode_step.argtypes = [pp] + [vp] * 15
+        L.swa_prepare.restype = ctypes.c_int
+        L.swa_prepare.argtypes = []
         L.swa_compact_kv.restype = ctypes.c_int
         L.swa_compact_kv.argtypes = [pp] + [vp] * 9
         L.swa_quantize_kv.restype = ctypes.c_int
@@ -141,7 +144,11 @@ def swa_workspace_init(params: SwaParams, workspace: torch.Tensor, stream=None) 
            "swa_workspace_init")
 
 
-def swa_check_status(params: SwaParams, workspace: torch.Tensor, stream=None) -> int:
+def swa_prepare() -> None:
+    _check(lib().swa_prepare(), "swa_prepare")
+
+
+def swa_check_status(params: SwaParams, workspace: Optional[torch.Tensor], stream=None) -> int:
     st = ctypes.c_int32(0)
     _check(lib().swa_check_status(ctypes.byref(params), _ptr(workspace), _stream(stream),
                                   ctypes.byref(st)), "swa_check_status")

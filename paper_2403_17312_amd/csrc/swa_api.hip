@@ -1,6 +1,7 @@
 // C-ABI entry points: argument validation on the host, then kernel launches on the
 // caller's stream.  Nothing here allocates, synchronises (except
-// swa_check_status) or reads device memory.
+// swa_check_status) or reads device memory.  Process-wide state: the table of raised LDS
+// limits.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -38,13 +39,8 @@ int decode_stash_rows(const swa_params& p)
 {
     // window + a margin for evictions a little behind it; bounded so LDS keeps several
     // workgroups per CU; never more than the cache can hold
-    static const int forced = [] {
-        const char* e = getenv("SWA_STASH_ROWS");   // tuning override, multiple of 16 in 0..96
-        return e ? atoi(e) : -1;
-    }();
     int rows = p.w < 0 ? 48 : ((p.w + 16 + 15) / 16) * 16;
     if (rows > 96) rows = 96;
-    if (forced >= 0 && forced <= 96) rows = (forced / 16) * 16;
     const int bound = (p.len_bound > 0 && p.len_bound < p.cap) ? p.len_bound : p.cap;
     if (rows > bound) rows = ((bound + 15) / 16) * 16;
     // long caches (first step after a prompt) take the gather schedule, which has no use for it
@@ -55,13 +51,6 @@ int decode_stash_rows(const swa_params& p)
 
 int decode_block_threads(int64_t pairs, int len_bound, bool kv_int8)
 {
-    // Tuning override (128, 256 or 512), read once.
-    static const int forced = [] {
-        const char* e = getenv("SWA_DECODE_NT");
-        const int v = e ? atoi(e) : 0;
-        return (v == 128 || v == 256 || v == 512) ? v : 0;
-    }();
-    if (forced) return forced;
     // Measured on MI355X (all five workloads): caches of a thousand slots and more (the first
     // step after a prompt, low sparsity) want 512 threads per pair, shorter ones 256; the pair
     // count matters little.
@@ -178,6 +167,11 @@ int swa_workspace_init(const swa_params* params, void* workspace, void* stream)
     if (rc != SWA_OK) return rc;
     if (!workspace) return SWA_ERR_NULL;
     return swa::launch_workspace_init(*params, workspace, static_cast<hipStream_t>(stream));
+}
+
+int swa_prepare(void)
+{
+    return swa::prepare_decode();
 }
 
 int swa_check_status(const swa_params* params, void* workspace, void* stream, int32_t* status_out)

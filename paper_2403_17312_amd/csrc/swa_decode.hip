@@ -1102,6 +1102,56 @@ static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes,
     }
 }
 
+// Raise the dynamic-LDS limit of every instantiation to what the device allows next to the
+// kernel's static LDS, so that no later launch has to (a launch inside a stream capture then
+// makes no runtime call besides the launch itself).
+template <typename T, int D, int NT, bool RING>
+static int prepare_one()
+{
+    auto kern = swa_decode_kernel<T, D, NT, RING>;
+    hipFuncAttributes fa;
+    if (hipFuncGetAttributes(&fa, reinterpret_cast<const void*>(kern)) != hipSuccess) {
+        (void)hipGetLastError();
+        return SWA_ERR_HIP;
+    }
+    int dev = 0, lds_max = 0;
+    if (hipGetDevice(&dev) != hipSuccess ||
+        hipDeviceGetAttribute(&lds_max, hipDeviceAttributeMaxSharedMemoryPerBlock, dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return SWA_ERR_HIP;
+    }
+    const long long room = (long long)lds_max - (long long)fa.sharedSizeBytes;
+    if (room <= 48 * 1024) return SWA_OK;
+    return ensure_dynamic_lds(reinterpret_cast<const void*>(kern), (size_t)room);
+}
+
+template <typename T, int D>
+static int prepare_t()
+{
+    int rc = prepare_one<T, D, 128, false>();
+    if (rc == SWA_OK) rc = prepare_one<T, D, 256, false>();
+    if (rc == SWA_OK) rc = prepare_one<T, D, 512, false>();
+    if constexpr (Elem<T>::kBytes != 1) {
+        if (rc == SWA_OK) rc = prepare_one<T, D, 128, true>();
+        if (rc == SWA_OK) rc = prepare_one<T, D, 256, true>();
+        if (rc == SWA_OK) rc = prepare_one<T, D, 512, true>();
+    }
+    return rc;
+}
+
+int prepare_decode()
+{
+    int rc = prepare_t<F32, 64>();
+    if (rc == SWA_OK) rc = prepare_t<F32, 128>();
+    if (rc == SWA_OK) rc = prepare_t<F16, 64>();
+    if (rc == SWA_OK) rc = prepare_t<F16, 128>();
+    if (rc == SWA_OK) rc = prepare_t<BF16, 64>();
+    if (rc == SWA_OK) rc = prepare_t<BF16, 128>();
+    if (rc == SWA_OK) rc = prepare_t<Q8, 64>();
+    if (rc == SWA_OK) rc = prepare_t<Q8, 128>();
+    return rc;
+}
+
 int launch_decode(const swa_params& p, float scale, const void* q, const void* k_new, const void* v_new,
                   void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
                   const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,

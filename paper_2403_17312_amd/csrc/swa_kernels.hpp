@@ -9,8 +9,13 @@
 
 namespace swa {
 
-// Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.
+// Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.  The
+// limits already granted are remembered per process (one mutex-guarded table): the only state
+// the library keeps.
 int ensure_dynamic_lds(const void* kernel, size_t bytes);
+
+// Raises that limit for every instantiation of the decode kernel on the current device.
+int prepare_decode();
 
 // Threads per workgroup of the decode kernel for this many (sequence, head) pairs, this bound on
 // the cached length and this cache format.

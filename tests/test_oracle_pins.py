@@ -84,14 +84,20 @@ def test_even_split_selection_keeps_k_local_and_k_global(oracle):
 
 
 def test_even_split_mode_of_algorithm_1(oracle):
-    # Alg. 1 line 1: k = nint(n r / 2) local and as many global tokens.  With
-    # w = k and a budget of 2k the generalised rule gives exactly that split.
-    for n, r_bp in [(100, 2000), (257, 2000), (64, 5000)]:
-        k = (n * r_bp + 10000) // 20000
-        # choose sparsity so that nint(n r) == 2k (true whenever n r /2 is not near .5)
-        keep, nl, ng = oracle.budget(n, n, k, 10000 - r_bp)
-        if keep == 2 * k:
-            assert (nl, ng) == (k, k)
+    # Alg. 1 line 1: k = nint(n r / 2) local and as many global tokens.  With w = k and a budget of
+    # 2k the generalised rule (independent window) gives exactly that split whenever
+    # nint(n r) == 2 nint(n r / 2); where the two roundings part, only the even-split mode
+    # (w = -1) follows Algorithm 1 and the generalised rule keeps nint(n r) tokens.
+    agree = [(100, 2000, 10), (64, 5000, 16), (5, 4000, 1), (4000, 1000, 200)]
+    for n, r_bp, k in agree:
+        assert k == (n * r_bp + 10000) // 20000
+        assert oracle.budget(n, n, k, 10000 - r_bp) == (2 * k, k, k), (n, r_bp)
+        assert oracle.budget(n, n, -1, 10000 - r_bp) == (2 * k, k, k), (n, r_bp)
+    # n r = 51.4 -> 51 but n r / 2 = 25.7 -> 26; 102.6 -> 103 but 51.3 -> 51; 205 but 102.5 -> 103
+    part = [(257, 2000, 26, 51), (513, 2000, 51, 103), (1025, 2000, 103, 205)]
+    for n, r_bp, k, keep in part:
+        assert oracle.budget(n, n, k, 10000 - r_bp) == (keep, k, keep - k), (n, r_bp)
+        assert oracle.budget(n, n, -1, 10000 - r_bp) == (2 * k, k, k), (n, r_bp)
 
 
 # --------------------------------------------------------------------------
