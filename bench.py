@@ -7,12 +7,15 @@ compaction, for all b*h (sequence, head) pairs of one layer.  By default that is
 ONE kernel (swa_decode_step with SWA_FUSE_COMPACTION); --step-mode split runs
 swa_decode_step followed by swa_compact_kv instead.
 
-The timed region walks complete decode trajectories of the workload (first
-step right after the prompt, then the steady state with compaction every
+The timed region walks the workload's decode trajectory from the prompt on
+(first step right after the prompt, then the steady state with compaction every
 step).  To keep the data HBM-cold the way a multi-layer model does, R
 independent replicas of the layer state are stepped round-robin (replica = one
-layer's cache): step i works on replica i % R at trajectory step i // R.
-Inputs are resident in HBM before the timed region starts.
+layer's cache): step i works on replica i % R at trajectory step i // R.  R
+follows from BYTES, never from --steps: the R consecutive steps of one sweep
+must touch at least SWEEP_MIN_BYTES of distinct cache (four times the 256 MB
+Infinity Cache), and R >= 2.  Inputs are resident in HBM before the timed
+region starts.
 
 Prints ONE JSON line (see README / DESIGN for the fields).
 """
@@ -30,6 +33,8 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published peak
+SWEEP_MIN_BYTES = 1 << 30   # distinct bytes one sweep over the replicas must touch (4 x the Infinity Cache)
+HEADLINE = "c5_llama7b_sp80"   # the largest single-GPU workload (b = 256, mixed prompts 512..2048)
 
 
 def simulate_lengths(B, wl, lens, compact_every=1):
@@ -133,29 +138,52 @@ class Replica:
         self.compact(B, t)
 
 
+_PROMPTS = {}
+
+
+def prompt_of(wl, W):
+    """Prompt state of a workload; the three sparsities of config 5 share one prompt."""
+    key = (wl.config_id, wl.seed, wl.b, wl.h, wl.d, wl.dtype, wl.prompt_lo, wl.prompt_hi, wl.steps, wl.w, wl.hh_frac)
+    if key not in _PROMPTS:
+        _PROMPTS.clear()                      # one prompt resident at a time (config 5: 10 GB)
+        _PROMPTS[key] = W.make_prompt(wl, "cuda")
+    return _PROMPTS[key]
+
+
+def replicas_for(step_bytes):
+    """Replica count from bytes alone: the R steps of one sweep touch R x (one step's working set) of
+    distinct memory, which must reach SWEEP_MIN_BYTES even for the lightest step; at least two."""
+    return max(2, math.ceil(SWEEP_MIN_BYTES / max(1, min(step_bytes))))
+
+
 def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True, kv_int8=False,
                    compact_every=1):
+    """Times `steps` decode steps (None = whole trajectories on every replica) after `warmup` untimed ones."""
     dev = "cuda"
     T = wl.steps
-    R = max(1, math.ceil(steps / T))
-    Rw = max(1, math.ceil(warmup / T)) if warmup > 0 else 0
-    prompt = W.make_prompt(wl, dev)
+    prompt = prompt_of(wl, W)
     lens = prompt["lengths"]
     inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(T)]
     q_tail = W.make_q_tail(wl, prompt["mu"], wl.prefill_R) if wl.prefill_R > 0 else None
     ms, keeps = simulate_lengths(B, wl, lens, compact_every)
     len_bounds = [max(m_t) for m_t in ms]
+    window_rows = min(max(wl.w, 1), B.SWA_MAX_WINDOW_ROWS) if fused == "window" else 0
+
+    def abp(m, k):
+        return W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k, kv_int8, window_rows)
+
+    step_bytes = [sum(wl.h * abp(m, k) for m, k in zip(ms[t], keeps[t])) for t in range(T)]
+    R = replicas_for(step_bytes)
+    if steps is None:
+        steps = T * R
+    steps = min(steps, T * R)                 # a trajectory has T steps; more would need more replicas
+    warmup = min(warmup, T * R)
 
     def fresh(n):
         reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8, compact_every) for _ in range(n)]
         for r in reps:
             r.finish_prompt(q_tail)
         return reps
-
-    window_rows = min(max(wl.w, 1), B.SWA_MAX_WINDOW_ROWS) if fused == "window" else 0
-
-    def abp(m, k):
-        return W.algorithmic_bytes_per_pair(wl.d, wl.elem_bytes, m, k, kv_int8, window_rows)
 
     def run(reps, count):
         n = len(reps)
@@ -164,9 +192,9 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
             q, kn, vn = inputs[t]
             reps[r].step(B, t, q, kn, vn)
 
-    # -------- warm-up on its own replicas (also raises the LDS limit before any capture)
-    if Rw:
-        wreps = fresh(Rw)
+    # -------- warm-up: the first `warmup` steps of the same schedule, on replicas of their own
+    if warmup > 0:
+        wreps = fresh(min(R, warmup))          # fewer steps than replicas: every one is a first step
         run(wreps, warmup)
         torch.cuda.synchronize()
         del wreps
@@ -213,6 +241,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         e1.record()
         torch.cuda.synchronize()
         t_wall1 = time.perf_counter()
+        del g
     else:
         t_wall0 = time.perf_counter()
         e0.record()
@@ -227,16 +256,15 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     del reps
 
     # -------- accounting
-    kv_tokens = 0
-    alg_bytes = 0
-    for i in range(steps):
-        t = i // R
-        kv_tokens += sum(ms[t])
-        for m, k in zip(ms[t], keeps[t]):
-            alg_bytes += wl.h * abp(m, k)
+    kv_tokens = sum(sum(ms[i // R]) for i in range(steps))
+    alg_bytes = sum(step_bytes[i // R] for i in range(steps))
+    sweep = [step_bytes[i // R] for i in range(steps)]
+    min_sweep = min(sum(sweep[j:j + R]) for j in range(0, max(1, steps - R + 1)))
 
     res = {
-        "workload": wl.name, "steps": steps, "replicas": R, "mode": mode, "fused": fused,
+        "workload": wl.name, "steps": steps, "warmup": warmup, "replicas": R, "mode": mode, "fused": fused,
+        "trajectory_steps_covered": (steps + R - 1) // R, "min_sweep_bytes": min_sweep,
+        "cold": bool(min_sweep >= 2 * (256 << 20) or steps < R),
         "ms_per_step": total_ms / steps, "total_ms": total_ms, "host_wall_ms": wall_ms,
         "kv_tokens_per_s": kv_tokens / (total_ms * 1e-3),
         "generated_tokens_per_s": wl.b * steps / (total_ms * 1e-3),
@@ -276,12 +304,10 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         steady = [dec[i] for i in range(steps) if i // n > 0]
         res["decode_first_step_ms"] = sum(first) / max(1, len(first))
         res["decode_steady_ms"] = sum(steady) / max(1, len(steady)) if steady else None
-        first_bytes = sum(wl.h * abp(m, k)
-                          for m, k in zip(ms[0], keeps[0]))
-        res["decode_first_step_gbs"] = first_bytes / (res["decode_first_step_ms"] * 1e-3) / 1e9
+        res["decode_first_step_gbs"] = step_bytes[0] / (res["decode_first_step_ms"] * 1e-3) / 1e9
+        res["decode_steady_gbs"] = None
         if steady:
-            sb = [sum(wl.h * abp(m, k)
-                      for m, k in zip(ms[i // n], keeps[i // n])) for i in range(steps) if i // n > 0]
+            sb = [step_bytes[i // n] for i in range(steps) if i // n > 0]
             res["decode_steady_gbs"] = sum(sb) / (sum(steady) * 1e-3) / 1e9
         del reps
     torch.cuda.empty_cache()
@@ -391,12 +417,65 @@ def load_traffic(name):
         return None
 
 
+STEP_TEXT = {
+    "unordered": "swa_decode_step with SWA_FUSE_COMPACTION|SWA_UNORDERED (one kernel, hole-filling compaction, "
+                 "kept_idx not requested)",
+    "fused": "swa_decode_step with SWA_FUSE_COMPACTION (one kernel, token-ordered compaction, kept_idx not "
+             "requested)",
+    "shared": "swa_decode_step with SWA_HEAD_SHARED (three launches around the head-summed importance, "
+              "hole-filling compaction)",
+    "window": "swa_decode_step_window (strict local attention sum over min(w, 64) rows, hole-filling compaction)",
+    "split": "swa_decode_step + swa_compact_kv",
+}
+
+
+def roofline_of(res, step_mode, kv_int8, wl_name):
+    """Roofline object of the decode kernel for one timed run.  One-kernel forms: the step IS the
+    kernel, so the HIP-event time of the timed region divided by the number of launches is its
+    average launch duration (inter-kernel gaps included, hence an upper bound).  Two-call form:
+    per-launch event brackets around swa_decode_step."""
+    one_kernel = step_mode in ("unordered", "fused", "window")
+    dec_ms = res["ms_per_step"] if one_kernel else res["decode_kernel_ms_avg"]
+    achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
+    tag = ("" if step_mode == "unordered" else "_" + step_mode) + ("_q8" if kv_int8 else "")
+    traffic = load_traffic(wl_name + tag) if one_kernel else None
+    first_frac = res["decode_first_step_gbs"] / HBM_PEAK_GBS if res.get("decode_first_step_gbs") else None
+    steady_frac = res["decode_steady_gbs"] / HBM_PEAK_GBS if res.get("decode_steady_gbs") else None
+    return {
+        "bound": "hbm", "kernel": "swa_decode_kernel",
+        "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+        "traffic": (traffic["fetch_bytes_per_launch"] + traffic["write_bytes_per_launch"]) if traffic else None,
+        "traffic_source": ("profiles/pmc_traffic.json: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this "
+                           "workload and step form, whole trajectories, scaled by a 1 GiB copy (not measured in "
+                           "this run)") if traffic else None,
+        "traffic_detail": traffic,
+        "alg_bytes_per_launch": res["alg_bytes_per_step"], "avg_launch_ms": dec_ms,
+        "timing": ("HIP events around the timed region on the launch stream / launches" if one_kernel
+                   else "HIP events around every swa_decode_step launch"),
+        "first_step_gbs": res.get("decode_first_step_gbs"), "steady_gbs": res.get("decode_steady_gbs"),
+        "first_step_frac": first_frac, "steady_frac": steady_frac,
+    }
+
+
+def summary_of(res, step_mode, kv_int8, wl_name):
+    r = roofline_of(res, step_mode, kv_int8, wl_name)
+    return {"step_mode": step_mode, "steps": res["steps"], "replicas": res["replicas"], "cold": res["cold"],
+            "kv_tokens_per_s": res["kv_tokens_per_s"], "ms_per_step": res["ms_per_step"],
+            "decode_kernel_ms_avg": res.get("decode_kernel_ms_avg"),
+            "compact_kernel_ms_avg": res.get("compact_kernel_ms_avg"),
+            "whole_step_alg_gbs": res["alg_gbs_whole_step"], "prefill_seed_ms": res["prefill_seed_ms"],
+            "roofline": {k: r[k] for k in ("bound", "achieved", "peak", "unit", "frac", "traffic", "alg_bytes_per_launch",
+                                           "avg_launch_ms", "first_step_frac", "steady_frac")}}
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=None, help="timed steps (default: 16 trajectories' worth)")
+    ap.add_argument("--steps", type=int, default=None,
+                    help="timed steps of the headline workload, taken from the prompt on (default: whole "
+                         "trajectories on every replica)")
     ap.add_argument("--warmup", type=int, default=None)
-    ap.add_argument("--config", default="c2_opt6p7b")
+    ap.add_argument("--config", default=HEADLINE)
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
     ap.add_argument("--step-mode", choices=["unordered", "fused", "split", "shared", "window"], default="unordered",
                     help="fused: one kernel per step, cache kept in token order; unordered: one kernel per "
@@ -416,8 +495,10 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
-    ap.add_argument("--others", default="c3_opt13b,c4_opt30b,c5_llama7b_sp50,c5_llama7b_sp80,c5_llama7b_sp90",
+    ap.add_argument("--others", default="c5_llama7b_sp50,c5_llama7b_sp90,c4_opt30b,c3_opt13b,c2_opt6p7b",
                     help="comma list of further workloads summarised in the same line ('' = none)")
+    ap.add_argument("--ordered-forms", default="fused,split",
+                    help="further step forms timed beside --step-mode for every workload ('' = none)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
@@ -431,93 +512,92 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     B.lib()
     torch.cuda.set_device(0)
+    B.swa_prepare()                      # LDS limits raised before anything is captured
 
     wl = W.CONFIGS[args.config]
-    steps = args.steps if args.steps is not None else wl.steps * max(1, 512 // wl.steps)
-    warmup = args.warmup if args.warmup is not None else wl.steps
-    fused = args.step_mode if args.step_mode != "split" else False
+    warmup = args.warmup if args.warmup is not None else 8
+    fused_of = lambda sm: sm if sm != "split" else False
     if args.compact_every != 1 and args.step_mode != "split":
         print("bench.py: --compact-every needs --step-mode split (the fused forms compact every step)", file=sys.stderr)
         sys.exit(2)
-    res = bench_workload(wl, steps, warmup, args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8,
-                         compact_every=args.compact_every)
-
-    # Average launch duration of the dominant kernel.  Fused mode: the step IS one kernel, so the
-    # HIP-event time of the graph replay divided by the number of launches is that kernel's
-    # average duration (inter-kernel gaps included, hence an upper bound); it agrees with
-    # rocprofv3's per-kernel average (profiles/).  Split mode: per-launch event brackets.
-    dec_ms = res["ms_per_step"] if fused else res["decode_kernel_ms_avg"]
-    achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
-    # measured traffic is stored per (workload, way of issuing the step)
-    tag = ("" if args.step_mode == "unordered" else "_" + args.step_mode) + ("_q8" if args.kv_int8 else "")
-    traffic = load_traffic(wl.name + tag) if args.step_mode in ("unordered", "fused", "window") else None
+    extra_forms = [x for x in args.ordered_forms.split(",") if x and x != args.step_mode]
+    if args.compact_every != 1 or args.step_mode in ("shared", "window"):
+        extra_forms = []
+    res = bench_workload(wl, args.steps, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
+                         kv_int8=args.kv_int8, compact_every=args.compact_every)
+    steps = res["steps"]
+    roof = roofline_of(res, args.step_mode, args.kv_int8, wl.name)
     line = {
         "metric": "SWA decode-step KV tokens/s",
         "value": res["kv_tokens_per_s"],
         "unit": "KV tokens/s",
-        "n_gpus": 1, "steps": steps, "warmup": warmup,
+        "n_gpus": 1, "steps": steps, "warmup": res["warmup"],
         "ms_per_step": res["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": wl.dtype + ("+u8kv" if args.kv_int8 else ""), "data": "synthetic",
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
-                   "replicas": res["replicas"], "launch": args.mode, "compact_every": args.compact_every,
-                   "step": {"unordered": "swa_decode_step with SWA_FUSE_COMPACTION|SWA_UNORDERED (one kernel, "
-                                         "hole-filling compaction, kept_idx not requested)",
-                            "fused": "swa_decode_step with SWA_FUSE_COMPACTION (one kernel, token-ordered "
-                                     "compaction, kept_idx not requested)",
-                            "shared": "swa_decode_step with SWA_HEAD_SHARED (two launches around the "
-                                      "head-summed importance, hole-filling compaction)",
-                            "window": "swa_decode_step_window (strict local attention sum over min(w, 64) rows, "
-                                      "hole-filling compaction)",
-                            "split": "swa_decode_step + swa_compact_kv"}[args.step_mode]
+                   "replicas": res["replicas"], "cold": res["cold"], "min_sweep_bytes": res["min_sweep_bytes"],
+                   "timed": f"trajectory steps 0..{res['trajectory_steps_covered'] - 1} (from the prompt on) of "
+                            f"{res['replicas']} replicas, round-robin",
+                   "launch": args.mode, "compact_every": args.compact_every,
+                   "step": STEP_TEXT[args.step_mode]
                            + ("; 8-bit compressed cache (swa_quantize_kv once, then swa_decode_step_q8)"
                               if args.kv_int8 else "")},
-        "roofline": {
-            "bound": "hbm", "kernel": "swa_decode_kernel",
-            "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-            "traffic": (traffic["fetch_bytes_per_launch"] + traffic["write_bytes_per_launch"]) if traffic else None,
-            "traffic_detail": traffic,
-            "alg_bytes_per_launch": res["alg_bytes_per_step"], "avg_launch_ms": dec_ms,
-            "first_step_gbs": res.get("decode_first_step_gbs"), "steady_gbs": res.get("decode_steady_gbs"),
-        },
+        "roofline": roof,
         "whole_step_alg_gbs": res["alg_gbs_whole_step"],
         "generated_tokens_per_s": res["generated_tokens_per_s"],
-        "detail": {k: res[k] for k in ("decode_kernel_ms_avg", "compact_kernel_ms_avg", "decode_first_step_ms",
-                                       "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
-                                       "prefill_seed_ms", "quantize_kv_ms")},
+        "detail": {k: res.get(k) for k in ("decode_kernel_ms_avg", "compact_kernel_ms_avg", "decode_first_step_ms",
+                                           "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
+                                           "prefill_seed_ms", "quantize_kv_ms")},
     }
     ceil_gbs = stream_read_ceiling(torch, B)
     line["roofline"]["measured_stream_read_gbs"] = ceil_gbs
-    line["roofline"]["frac_of_measured_stream_read"] = achieved / ceil_gbs
+    line["roofline"]["frac_of_measured_stream_read"] = roof["achieved"] / ceil_gbs
     line["pair_rows_per_s"] = res["kv_tokens_per_s"] * wl.h
+
+    def seed_detail(o, r):
+        # one read of the prompt's keys and 2 R s d flops per pair
+        lens = W.prompt_lengths(o).tolist()
+        kb = sum(lens) * o.h * o.d * o.elem_bytes
+        fl = 2.0 * o.prefill_R * sum(lens) * o.h * o.d
+        sec = r["prefill_seed_ms"] * 1e-3
+        return {"ms": r["prefill_seed_ms"], "gbs_one_read_of_K": kb / sec / 1e9, "frac_of_hbm_peak": kb / sec / 1e9 / HBM_PEAK_GBS,
+                "tflops_one_pass": fl / sec / 1e12}
+
     if res["prefill_seed_ms"]:
-        # one read of the prompt's keys and 2 R s d flops per pair per pass (two passes run)
-        lens = W.prompt_lengths(wl).tolist()
-        kb = sum(lens) * wl.h * wl.d * wl.elem_bytes
-        fl = 2.0 * 2.0 * wl.prefill_R * sum(lens) * wl.h * wl.d
-        line["detail"]["prefill_seed_gbs"] = kb / (res["prefill_seed_ms"] * 1e-3) / 1e9
-        line["detail"]["prefill_seed_tflops"] = fl / (res["prefill_seed_ms"] * 1e-3) / 1e12
+        line["detail"]["prefill_seed"] = seed_detail(wl, res)
     if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
+
+    # the same workload in the forms that keep the cache in token order
+    forms = []
+    for sm in extra_forms:
+        r = bench_workload(wl, args.steps, warmup, args.mode, torch, B, W, fused=fused_of(sm), kv_int8=args.kv_int8)
+        forms.append(summary_of(r, sm, args.kv_int8, wl.name))
+    if forms:
+        line["other_step_forms"] = forms
+
     if not args.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)
 
     others = []
     for name in [x for x in args.others.split(",") if x and x != args.config]:
         o = W.CONFIGS[name]
-        k = o.steps * max(1, 256 // o.steps)
         if args.kv_int8 and o.dtype != "f16":
             continue
-        r = bench_workload(o, k, min(o.steps, 32), args.mode, torch, B, W, fused=fused, kv_int8=args.kv_int8,
-                           compact_every=args.compact_every)
-        a = r["alg_bytes_per_step"] / ((r["ms_per_step"] if fused else r["decode_kernel_ms_avg"]) * 1e-3) / 1e9
-        others.append({"workload": name, "steps": k, "kv_tokens_per_s": r["kv_tokens_per_s"],
-                       "ms_per_step": r["ms_per_step"], "decode_kernel_ms_avg": r["decode_kernel_ms_avg"],
-                       "compact_kernel_ms_avg": r["compact_kernel_ms_avg"],
-                       "roofline_frac": a / HBM_PEAK_GBS, "first_step_gbs": r.get("decode_first_step_gbs"),
-                       "steady_gbs": r.get("decode_steady_gbs"), "whole_step_alg_gbs": r["alg_gbs_whole_step"],
-                       "prefill_seed_ms": r["prefill_seed_ms"]})
+        entry = {"workload": name}
+        for sm in [args.step_mode] + extra_forms:
+            r = bench_workload(o, None, min(o.steps, 8), args.mode, torch, B, W, fused=fused_of(sm),
+                               kv_int8=args.kv_int8, compact_every=args.compact_every)
+            sm_sum = summary_of(r, sm, args.kv_int8, name)
+            if sm == args.step_mode:
+                entry.update(sm_sum)
+                if r["prefill_seed_ms"]:
+                    entry["prefill_seed"] = seed_detail(o, r)
+            else:
+                entry.setdefault("other_step_forms", []).append(sm_sum)
+        others.append(entry)
     if others:
         line["other_workloads"] = others
     if args.copy_calibration:

@@ -46,10 +46,20 @@ class Report:
     near_tie_flips: int = 0
     evictions: int = 0
     moved_rows: int = 0
+    out_elems: int = 0
+    out_over_2e3: int = 0        # outputs whose |delta| exceeds the 2e-3 bar stated for fp16 (bf16 runs report it)
+    twin_steps: int = 0          # steps on which the twin state (no debug outputs) was compared bit for bit
 
 
 def _np64(t: torch.Tensor) -> np.ndarray:
-    return t.detach().to("cpu").to(torch.float64).numpy().copy()
+    # widened on the device the tensor lives on (exact), then copied to the host
+    return t.detach().to(torch.float64).to("cpu").numpy().copy()
+
+
+def _same_bits(a: torch.Tensor, b: torch.Tensor) -> bool:
+    """Bitwise equality (NaN-filled slack compares equal to itself)."""
+    it = {1: torch.uint8, 2: torch.int16, 4: torch.int32}[a.element_size()]
+    return a.dtype == b.dtype and torch.equal(a.view(it), b.view(it))
 
 
 def _sub(t: torch.Tensor, seqs, heads) -> torch.Tensor:
@@ -65,7 +75,7 @@ def new_state(wl: W.Workload, prompt: dict, debug_probs: bool = True) -> B.Decod
     return st
 
 
-def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
+def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str, rep=None):
     atol, rel_elem, rtol = TOL[dtype]
     err = np.abs(out_gpu - out_ref)
     assert np.all(np.isfinite(out_gpu)), f"{what}: non-finite output at {np.argwhere(~np.isfinite(out_gpu))[:8].tolist()}"
@@ -73,6 +83,9 @@ def check_out(out_gpu: np.ndarray, out_ref: np.ndarray, dtype: str, what: str):
     excess = err - (atol + rel_elem * np.abs(out_ref))
     assert excess.max() <= 0, f"{what}: max abs {err.max():.3e} exceeds {atol} + {rel_elem:.2e}*|ref|"
     assert rel.max() <= rtol, f"{what}: rel L2 {rel.max():.3e} > {rtol}"
+    if rep is not None:
+        rep.out_elems += int(err.size)
+        rep.out_over_2e3 += int(np.count_nonzero(err > 2e-3))
     return float(err.max()), float(rel.max())
 
 
@@ -81,8 +94,15 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  compact_every: int = 1, slack: str = "nan", check_steps=None,
                  prompt: Optional[dict] = None, verbose: bool = False,
                  use_len_bound: bool = False, fused: bool = False, unordered: bool = False,
-                 sparsity_of_step=None, head_shared: bool = False, kv_int8: bool = False) -> Report:
-    """Runs the whole trajectory on the GPU; checks the sampled pairs every step."""
+                 sparsity_of_step=None, head_shared: bool = False, kv_int8: bool = False,
+                 twin: bool = False, twin_kv_every: int = 1) -> Report:
+    """Runs the whole trajectory on the GPU; checks the sampled pairs every step.
+
+    twin: a second full-size state is stepped beside the checked one in the call form that
+    bench.py times - no debug weights and, in the fused forms, no kept_idx - and must stay
+    bit-identical to it on EVERY pair (outputs, importance, positions and lengths every step; keys
+    and values every twin_kv_every-th step and at the end).  The checked state is compared with
+    the oracle, so the timed call form is tied to the oracle through it."""
     steps = wl.steps if steps is None else steps
     seqs = list(range(wl.b)) if seqs is None else list(seqs)
     heads = list(range(wl.h)) if heads is None else list(heads)
@@ -102,6 +122,15 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             B.swa_workspace_init(st.params, st.workspace)
     else:
         assert not unordered
+    tw = None
+    if twin:
+        tw = new_state(wl, dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone()),
+                       debug_probs=False)
+        tw.params.flags = st.params.flags
+        tw.kept_idx.fill_(-7)                                  # must stay untouched in the fused forms
+        if head_shared:
+            tw.workspace = torch.zeros((B.swa_workspace_bytes(tw.params),), dtype=torch.uint8, device=device)
+            B.swa_workspace_init(tw.params, tw.workspace)
     # Unordered compaction keeps the cache as a set: every GPU tensor is brought into token order
     # (sorted by pos) before it is compared with the oracle, whose cache is always in token order.
     seqs_t = torch.tensor(seqs, device=device)
@@ -124,8 +153,12 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         for i, L in enumerate(len_o):
             assert np.all(S_gpu[i, :, L:] == 0.0)
         score_o = S_gpu.copy()                                   # adopt
+        if tw is not None:
+            tw.prefill_scores(q_tail)
     else:
         st.score.zero_()
+        if tw is not None:
+            tw.score.zero_()
 
     qp = None
     if kv_int8:
@@ -133,6 +166,8 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
         # Parameters and codes must equal the oracle's bit for bit; from here on the oracle's cache
         # holds the de-quantised values, which are what the compressed attention reads.
         st.quantize()
+        if tw is not None:
+            tw.quantize()
         qp_g = [_sub(st.qparams[k], seqs_t, heads_t).cpu().numpy() for k in range(4)]
         lamK, zK = O.kv_qparams(K_o, len_o)
         lamV, zV = O.kv_qparams(V_o, len_o)
@@ -168,6 +203,15 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             st.decode_compact_step(q, kn, vn)        # swaps cache_len / kept_cnt afterwards
         else:
             st.decode_step(q, kn, vn)
+        if tw is not None:
+            tw.seq_len += 1
+            tw.params.sparsity_bp = sp_t
+            tw.params.len_bound = st.params.len_bound
+            if fused:
+                tw.decode_compact_step(q, kn, vn, want_idx=False)
+            else:
+                tw.decode_step(q, kn, vn)
+            assert _same_bits(tw.out, st.out), f"step {t}: twin output differs"
         for s_i in range(wl.b):
             m_i = host_len[s_i] + 1
             host_len[s_i] = (B.swa_budget(prompt["lengths"][s_i] + t + 1, m_i, wl.w, sp_t)[0]
@@ -272,7 +316,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                         rep.near_tie_flips += len(diff) // 2
             # (iii) output on the GPU's kept set
             out_ref = O.sparse_attention(q_o, K_o, V_o, kept_g, cnt_g, wl.scale)
-            ea, er = check_out(out_g, out_ref, wl.dtype, f"step {t} out")
+            ea, er = check_out(out_g, out_ref, wl.dtype, f"step {t} out", rep)
             rep.max_out_abs, rep.max_out_rel = max(rep.max_out_abs, ea), max(rep.max_out_rel, er)
 
         # ---- adopt the GPU's importance values; compaction ----------------------------
@@ -285,6 +329,8 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                     rep.moved_rows += int(np.sum(kept_g[i, hd, :c] != np.arange(c)))
             if not fused:
                 st.compact()
+                if tw is not None:
+                    tw.compact()
             O.compact(K_o, V_o, score_o, pos_o, kept_g, cnt_g, len_o)
             assert np.array_equal(st.cache_len[seqs_t].cpu().numpy(), len_o)
             if do_check:
@@ -307,11 +353,46 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                     assert np.array_equal(V_g[i, :, :L], V_o[i, :, :L]), f"step {t}: V after compaction"
                     assert np.array_equal(s_g[i, :, :L], score_o[i, :, :L]), f"step {t}: score after compaction"
                     assert np.array_equal(pos_g[i, :, :L], pos_o[i, :, :L]), f"step {t}: pos after compaction"
+        if tw is not None:
+            assert torch.equal(tw.cache_len, st.cache_len), f"step {t}: twin lengths differ"
+            assert _same_bits(tw.score, st.score) and _same_bits(tw.pos, st.pos), f"step {t}: twin importance/pos"
+            if (t + 1) % twin_kv_every == 0 or t == steps - 1:
+                assert _same_bits(tw.K, st.K) and _same_bits(tw.V, st.V), f"step {t}: twin K/V differ"
+            if fused:
+                assert bool((tw.kept_idx == -7).all()), "kept_idx was written although not requested"
+            rep.twin_steps += 1
         rep.steps += 1
         if verbose and (t % 16 == 0 or t == steps - 1):
             print(f"  [{wl.name}] step {t}: m={len_o.tolist()[:4]} ok", flush=True)
     assert st.check_status() == 0
+    if tw is not None:
+        assert tw.check_status() == 0
     return rep
+
+
+def run_every_pair(wl: W.Workload, steps: int, chunk: int, device="cuda", first_seq: int = 0,
+                   last_seq: Optional[int] = None, **kw) -> Report:
+    """Lock-step check of EVERY (sequence, head) pair of sequences first_seq..last_seq-1 over the
+    first `steps` decode steps (the step right after the prompt and the first steady ones), at
+    full size on the GPU.  The sequences are checked `chunk` at a time to bound host memory; the
+    GPU side is the same full-size trajectory for every chunk.  Stops at the first failure."""
+    last_seq = wl.b if last_seq is None else last_seq
+    prompt = W.make_prompt(wl, device, slack="zero")
+    total = Report()
+    for c0 in range(first_seq, last_seq, chunk):
+        seqs = list(range(c0, min(last_seq, c0 + chunk)))
+        pc = dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone(),
+                  cache_len=prompt["cache_len"].clone())
+        rep = run_lockstep(wl, device=device, steps=steps, seqs=seqs, prompt=pc, slack="zero", use_len_bound=True, **kw)
+        total.steps = rep.steps
+        total.pairs += rep.pairs
+        for f in ("max_prob_rel", "max_score_rel", "max_out_abs", "max_out_rel"):
+            setattr(total, f, max(getattr(total, f), getattr(rep, f)))
+        for f in ("near_tie_flips", "evictions", "moved_rows", "out_elems", "out_over_2e3"):
+            setattr(total, f, getattr(total, f) + getattr(rep, f))
+        print(f"  [{wl.name}] sequences {seqs[0]}..{seqs[-1]}: every head, {rep.steps} steps ok", flush=True)
+        del pc
+    return total
 
 
 def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[int] = None,
