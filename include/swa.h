@@ -10,7 +10,8 @@
  *   - `swa_params*` is a HOST pointer; every other pointer is a DEVICE pointer
  *     owned by the caller.  The library never allocates or frees device memory.
  *     The state it keeps per process is small and internal: which kernels have had
- *     their LDS limit raised.  Everything a call computes goes through its arguments.
+ *     their LDS limit raised, and the device address of the fixed scratch array of
+ *     swa_decode_step_static.  Everything a call computes goes through its arguments.
  *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).  Calls
  *     only enqueue work: they never synchronise and never read device memory on
  *     the host, so a sequence of calls can be captured into a HIP graph.  A decode
@@ -137,7 +138,8 @@ typedef struct {
 
 /*
  * One-time set-up on the current device, optional but needed before stream capture: raises the
- * LDS limit of every decode kernel to the device's maximum.  Host-side only; enqueues nothing.  Call it again after hipSetDevice
+ * LDS limit of every decode kernel to the device's maximum and looks up the scratch array of
+ * swa_decode_step_static.  Host-side only; enqueues nothing.  Call it again after hipSetDevice
  * to another GPU.
  */
 int swa_prepare(void);
@@ -154,6 +156,7 @@ int swa_workspace_init(const swa_params *params, void *workspace, void *stream);
 
 /* Synchronises `stream`, copies the sticky status bits to the host and clears them.
  * *status_out = SWA_OK or SWA_ERR_CAPACITY (some decode step met a full cache).
+ * workspace == NULL reads the status word of swa_decode_step_static on the current device.
  * This is the only entry point that blocks. */
 int swa_check_status(const swa_params *params, void *workspace, void *stream, int32_t *status_out);
 
@@ -210,6 +213,29 @@ int swa_decode_step(const swa_params *params, const void *q, const void *k_new, 
                     void *k_cache, void *v_cache, float *score, int32_t *pos, int32_t *cache_len,
                     const int32_t *seq_len, int32_t *kept_idx, int32_t *kept_cnt, void *out,
                     float *probs_dbg, void *workspace, void *stream);
+
+/*
+ * swa_decode_step for callers that cannot allocate device memory or carry a workspace around:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, steps, flag variants (SWA_KV_INT8 excepted) and results as swa_decode_step, without
+ * the workspace: status word, arrival counters and the head-shared slabs live in a fixed array
+ * of SWA_STATIC_SCRATCH_BYTES inside the library, one per GPU, held until the process ends.
+ *   - params whose swa_workspace_bytes() exceeds SWA_STATIC_SCRATCH_BYTES are refused with
+ *     SWA_ERR_CAPACITY before anything is enqueued (in practice: b beyond two million, or a
+ *     head-shared step whose b*h*cap slabs do not fit).
+ *   - Calls no hipMalloc/hipFree and no allocating routine; the first call on a device looks the
+ *     array's address up (swa_prepare does the same ahead of time).
+ *   - Every call on one GPU shares that GPU's array: calls that overlap in time on one GPU
+ *     (different streams, or graphs replayed concurrently) race.  Calls on one stream are safe.
+ *   - The two-call form enqueues one small fill kernel that zeroes the arrival counters first.
+ *   - The sticky status word is read with swa_check_status(params, NULL, stream, &st).
+ */
+#define SWA_STATIC_SCRATCH_BYTES (8u << 20)
+int swa_decode_step_static(const swa_params *params, const void *q, const void *k_new,
+                           const void *v_new, void *k_cache, void *v_cache, float *score,
+                           int32_t *pos, int32_t *cache_len, const int32_t *seq_len,
+                           int32_t *kept_idx, int32_t *kept_cnt, void *out, float *probs_dbg,
+                           void *stream);
 
 /*
  * In-place compaction of the cache to the kept set (the gather of Algorithm 1

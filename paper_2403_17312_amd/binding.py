@@ -30,12 +30,13 @@ SWA_HEAD_SHARED = 4
 SWA_MAX_UNORDERED_SLOTS = 7168
 SWA_KV_INT8 = 8
 SWA_MAX_WINDOW_ROWS = 64
+SWA_STATIC_SCRATCH_BYTES = 8 << 20
 
 DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SWA_BF16}
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
            "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read",
-           "swa_prepare"]
+           "swa_prepare", "swa_decode_step_static"]
 
 
 class SwaParams(ctypes.Structure):
@@ -79,6 +80,8 @@ def lib():
         L.swa_prefill_scores.argtypes = [pp, vp, ctypes.c_int32, vp, i32p, vp, vp, vp]
         L.swa_decode_step.restype = ctypes.c_int
         L.swa_decode_step.argtypes = [pp] + [vp] * 15
+        L.swa_decode_step_static.restype = ctypes.c_int
+        L.swa_decode_step_static.argtypes = [pp] + [vp] * 14
         L.swa_prepare.restype = ctypes.c_int
         L.swa_prepare.argtypes = []
         L.swa_compact_kv.restype = ctypes.c_int
@@ -146,6 +149,15 @@ def swa_workspace_init(params: SwaParams, workspace: torch.Tensor, stream=None) 
 
 def swa_prepare() -> None:
     _check(lib().swa_prepare(), "swa_prepare")
+
+
+def swa_decode_step_static(params: SwaParams, q, k_new, v_new, k_cache, v_cache, score, pos, cache_len,
+                           seq_len, kept_idx, kept_cnt, out, probs_dbg, stream=None) -> None:
+    _check(lib().swa_decode_step_static(ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                        _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(pos),
+                                        _ptr(cache_len), _ptr(seq_len), _ptr(kept_idx), _ptr(kept_cnt),
+                                        _ptr(out), _ptr(probs_dbg), _stream(stream)),
+           "swa_decode_step_static")
 
 
 def swa_check_status(params: SwaParams, workspace: Optional[torch.Tensor], stream=None) -> int:

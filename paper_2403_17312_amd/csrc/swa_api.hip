@@ -1,7 +1,7 @@
 // C-ABI entry points: argument validation on the host, then kernel launches on the
 // caller's stream.  Nothing here allocates, synchronises (except
 // swa_check_status) or reads device memory.  Process-wide state: the table of raised LDS
-// limits.
+// limits, and the per-device address of the static scratch array below.
 #include <math.h>
 #include <stdio.h>
 #include <stdlib.h>
@@ -58,6 +58,38 @@ int decode_block_threads(int64_t pairs, int len_bound, bool kv_int8)
     // 8-bit rows are half as long, so a workgroup has half the lanes' worth of work per row and
     // the fixed phases weigh more: smaller workgroups, more of them in flight.
     return (pairs >= 1024 && len_bound < 1024) ? 128 : 256;
+}
+
+// Scratch of swa_decode_step_static, the entry point that allocates nothing and takes no
+// workspace: status word, arrival counters and (head-shared step) the slabs between the launches.
+// One copy per GPU, alive until the process ends, shared by every call on that GPU.  In host code
+// this name is only a handle for hipGetSymbolAddress; kernels get the device address.
+static __device__ __align__(256) unsigned char scratch[SWA_STATIC_SCRATCH_BYTES];
+
+constexpr int kMaxDevices = 64;
+static void* g_scratch_ptr[kMaxDevices];      // device address of `scratch`, per device
+static std::mutex g_scratch_mu;
+
+// Device address of this device's scratch array (looked up once per device, with it current).
+static int static_scratch(void** out)
+{
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) {
+        (void)hipGetLastError();
+        return SWA_ERR_HIP;
+    }
+    if (dev < 0 || dev >= kMaxDevices) return SWA_ERR_BAD_SHAPE;
+    std::lock_guard<std::mutex> lock(g_scratch_mu);
+    if (!g_scratch_ptr[dev]) {
+        void* ptr = nullptr;
+        if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+            (void)hipGetLastError();
+            return SWA_ERR_HIP;
+        }
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return SWA_OK;
 }
 
 __global__ void swa_fill_zero_kernel(int32_t* p, int64_t n)
@@ -171,6 +203,9 @@ int swa_workspace_init(const swa_params* params, void* workspace, void* stream)
 
 int swa_prepare(void)
 {
+    void* ptr = nullptr;
+    int rc = swa::static_scratch(&ptr);
+    if (rc != SWA_OK) return rc;
     return swa::prepare_decode();
 }
 
@@ -178,7 +213,11 @@ int swa_check_status(const swa_params* params, void* workspace, void* stream, in
 {
     int rc = swa::validate(params);
     if (rc != SWA_OK) return rc;
-    if (!workspace || !status_out) return SWA_ERR_NULL;
+    if (!status_out) return SWA_ERR_NULL;
+    if (!workspace) {          // the status word of swa_decode_step_static on the current device
+        rc = swa::static_scratch(&workspace);
+        if (rc != SWA_OK) return rc;
+    }
     hipStream_t st = static_cast<hipStream_t>(stream);
     int32_t bits = 0;
     char* ws = static_cast<char*>(workspace) + swa::kWsStatusOffset;
@@ -285,6 +324,32 @@ int swa_decode_step(const swa_params* params, const void* q, const void* k_new, 
     if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;   // codes need their parameters
     return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
                          kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+int swa_decode_step_static(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                           void* k_cache, void* v_cache, float* score, int32_t* pos, int32_t* cache_len,
+                           const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
+                           float* probs_dbg, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (swa_workspace_bytes(params) > (size_t)SWA_STATIC_SCRATCH_BYTES) return SWA_ERR_CAPACITY;
+    void* ptr = nullptr;
+    rc = swa::static_scratch(&ptr);
+    if (rc != SWA_OK) return rc;
+    if (!(params->flags & SWA_FUSE_COMPACTION)) {
+        // The arrival counters must start at zero whatever an earlier call (of another shape, or
+        // one that was abandoned) left there.  A fill kernel, not a memset node: callers may
+        // capture this call into a graph.  The sticky status word is left alone.
+        hipLaunchKernelGGL(swa::swa_fill_zero_kernel, dim3((unsigned)((params->b + 255) / 256)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream),
+                           reinterpret_cast<int32_t*>(static_cast<char*>(ptr) + swa::kWsArriveOffset),
+                           (int64_t)params->b);
+        if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
+    }
+    return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
+                         kept_idx, kept_cnt, out, probs_dbg, ptr, stream);
 }
 
 int swa_decode_step_q8(const swa_params* params, const void* q, const void* k_new, const void* v_new,

@@ -11,7 +11,7 @@ namespace swa {
 
 // Raises the dynamic-LDS limit of a kernel when a launch needs more than the default.  The
 // limits already granted are remembered per process (one mutex-guarded table): the only state
-// the library keeps.
+// the library keeps besides the address of the static scratch array.
 int ensure_dynamic_lds(const void* kernel, size_t bytes);
 
 // Raises that limit for every instantiation of the decode kernel on the current device.
