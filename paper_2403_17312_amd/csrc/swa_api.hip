@@ -118,7 +118,7 @@ __global__ void __launch_bounds__(256) swa_stream_read_kernel(const Vec16* src, 
 #pragma unroll
         for (int u = 0; u < 8; ++u) {
             const size_t j = i + (size_t)u * 256;
-            v[u] = (j < vec_per_block) ? base[j] : Vec16{0u, 0u, 0u, 0u};
+            v[u] = (j < vec_per_block) ? load16_stream(base + j) : Vec16{0u, 0u, 0u, 0u};
         }
 #pragma unroll
         for (int u = 0; u < 8; ++u) acc += v[u].x ^ v[u].y ^ v[u].z ^ v[u].w;

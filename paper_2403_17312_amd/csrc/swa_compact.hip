@@ -64,8 +64,8 @@ __global__ void __launch_bounds__(NT) swa_compact_kernel(CompactArgs a)
             if (j < cnt) {
                 int src = idx[j];
                 src = src < 0 ? 0 : (src >= cap ? cap - 1 : src);
-                kk[u] = load16(Kp + (int64_t)src * ROWB + sub * 16);
-                vv[u] = load16(Vp + (int64_t)src * ROWB + sub * 16);
+                kk[u] = load16_stream(Kp + (int64_t)src * ROWB + sub * 16);
+                vv[u] = load16_stream(Vp + (int64_t)src * ROWB + sub * 16);
                 dst[u] = j;
             }
         }

@@ -111,10 +111,11 @@ __device__ __forceinline__ void merge_acc(float& M, float& S, float* acc, float 
 }
 
 // Register budget: five waves per SIMD (96 VGPRs) for the 16- and 32-bit caches, four (128) for
-// the 8-bit one, whose lanes carry 16 channels each; neither bound spills.  RING: the strict
+// the 8-bit one, whose lanes carry 16 channels each, and for the 512-thread workgroups that serve
+// long caches (two of them fill a CU's wave slots either way); none of the bounds spills.  RING: the strict
 // local attention sum, a separate instantiation so that the other forms carry none of its code.
 template <typename T, int D, int NT, bool RING>
-__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu(Elem<T>::kBytes == 1 ? 4 : 5)))
+__global__ void __launch_bounds__(NT) __attribute__((amdgpu_waves_per_eu((Elem<T>::kBytes == 1 || NT >= 512) ? 4 : 5)))
 swa_decode_kernel(DecodeArgs a)
 {
     // a.ring is non-NULL exactly when RING (the launcher picks the instantiation)
@@ -129,7 +130,10 @@ swa_decode_kernel(DecodeArgs a)
     constexpr bool kQ8 = Elem<T>::kBytes == 1;
     constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
     constexpr int UF = SWA_UF;              // key+value row pairs per group and pipeline stage (fused pass)
-    constexpr int UV = 4;                   // value rows in flight per group (gathered pass)
+    // The 512-thread instantiation (long caches: the step after a prompt) has 128 registers per
+    // lane and keeps twice as many rows in flight in the gathered pass and in the row moves.
+    constexpr bool kWide = NT >= 512;
+    constexpr int UV = kWide ? 8 : 4;       // value rows in flight per group (gathered pass)
     constexpr int SPF = 4;                  // importance values prefetched per thread
 
     extern __shared__ __align__(16) char smem[];
@@ -181,9 +185,8 @@ swa_decode_kernel(DecodeArgs a)
     // The first stage of the streaming pass is requested before the lengths are known (they are a
     // dependent round trip of their own): its rows exist whatever the length is (clamped to the
     // last slot), and whatever lies at or beyond `len` is replaced by the new row when the stage
-    // is reduced.  Volatile so that the loads stay up here; they are waited for at their first use.
+    // is reduced.  They are waited for at their first use.
     // (Not for the 8-bit cache: its lanes have no registers to spare, and it measured slower.)
-    typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
     constexpr bool kEarlyStage = !kQ8;
     Vec16 k0[UF], v0[UF];
     if (kEarlyStage && a.phase != 2) {
@@ -193,10 +196,8 @@ swa_decode_kernel(DecodeArgs a)
         for (int u = 0; u < UF; ++u) {
             int row = u * NG + grp;
             row = row < a.cap ? row : a.cap - 1;
-            const u32x4_t kk = *reinterpret_cast<const volatile u32x4_t*>(Kq + (int64_t)row * ROWB + sub * 16);
-            const u32x4_t vv = *reinterpret_cast<const volatile u32x4_t*>(Vq + (int64_t)row * ROWB + sub * 16);
-            k0[u] = Vec16{kk[0], kk[1], kk[2], kk[3]};
-            v0[u] = Vec16{vv[0], vv[1], vv[2], vv[3]};
+            k0[u] = load16_stream(Kq + (int64_t)row * ROWB + sub * 16);
+            v0[u] = load16_stream(Vq + (int64_t)row * ROWB + sub * 16);
         }
     }
 
@@ -324,8 +325,8 @@ swa_decode_kernel(DecodeArgs a)
                 for (int u = 0; u < UF; ++u) {
                     int row = base + u * NG + grp;
                     row = row < m ? row : len;
-                    kv[u] = load16(Kp + (int64_t)row * ROWB + sub * 16);
-                    vv[u] = load16(Vp + (int64_t)row * ROWB + sub * 16);
+                    kv[u] = load16_stream(Kp + (int64_t)row * ROWB + sub * 16);
+                    vv[u] = load16_stream(Vp + (int64_t)row * ROWB + sub * 16);
                 }
             };
             auto reduce_stage = [&](int base, Vec16(&kv)[UF], Vec16(&vv)[UF]) {
@@ -414,7 +415,10 @@ swa_decode_kernel(DecodeArgs a)
                 for (int u = 0; u < UK; ++u) {
                     const int row = base + u * NG + grp;
                     if (row < len) {
-                        kv[u] = load16(Kp + (int64_t)row * ROWB + sub * 16);
+                        // with fused compaction the key rows that change slot are read again soon:
+                        // plain loads leave them where the second read can find them
+                        kv[u] = fc ? load16(Kp + (int64_t)row * ROWB + sub * 16)
+                                   : load16_stream(Kp + (int64_t)row * ROWB + sub * 16);
                     } else {
                         kv[u] = nk;
                     }
@@ -812,6 +816,8 @@ swa_decode_kernel(DecodeArgs a)
         // ---- output ---------------------------------------------------------------------------
         // kept mass 1 - sum_E p_j decides whether the subtractive form is safe
         bool subtract = fused;
+        bool rows_moved = false;          // the output pass moved the value rows and the first key rows
+        constexpr int UM = kWide ? 8 : 4; // rows per group and batch when rows change slot
         float pe = 0.f;
         int ec = 0;
         if (fused) {
@@ -852,23 +858,52 @@ swa_decode_kernel(DecodeArgs a)
                 write_out(e, t / (1.f - pe));
             }
         } else {
-            // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i
+            // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i.
+            // Unordered layout with many evictions (the step after a prompt): the rows that change
+            // slot are moved inside this pass, so that the whole step needs one more memory round
+            // trip instead of four.  A value row that moves is stored to its final slot as soon as
+            // it has been accumulated (its destination is an evicted slot, which nobody reads), and
+            // the key rows of the first NG*UM movers are requested before the value rows and stored
+            // after the pass (sources lie at or above `keep`, destinations below: disjoint).
             __syncthreads();
+            rows_moved = kWide && fc && bag && have_list;
+            Vec16 kmv[UM];
+            int kdst[UM];
+            if (rows_moved) {
+#pragma unroll
+                for (int u = 0; u < UM; ++u) {
+                    const int k = u * NG + grp;
+                    kdst[u] = -1;
+                    if (k < n_moves) {
+                        int src = s_movers[k], dst = s_holes[k];
+                        src = src > len ? len : src;
+                        dst = dst >= keep ? keep - 1 : dst;
+                        kmv[u] = load16(Kp + (int64_t)src * ROWB + sub * 16);
+                        if (src == len) kmv[u] = nk;
+                        kdst[u] = dst;
+                    }
+                }
+            }
 #pragma unroll
             for (int e = 0; e < EPV; ++e) acc[e] = 0.f;
             float ps = 0.f;
             for (int j0 = 0; j0 < keep; j0 += NG * UV) {
                 Vec16 vv[UV];
                 float pw[UV];
+                int vdst[UV];
 #pragma unroll
                 for (int u = 0; u < UV; ++u) {
                     const int j = j0 + u * NG + grp;
+                    vdst[u] = -1;
                     if (j < keep) {
                         int idx = src_of(j);
                         idx = idx < 0 ? 0 : (idx > len ? len : idx);
                         pw[u] = s_p[idx];
-                        vv[u] = load16(Vp + (int64_t)idx * ROWB + sub * 16);
+                        // (plain loads under fused compaction: the rows that move are read again)
+                        vv[u] = fc ? load16(Vp + (int64_t)idx * ROWB + sub * 16)
+                                   : load16_stream(Vp + (int64_t)idx * ROWB + sub * 16);
                         if (idx == len) vv[u] = nv;
+                        if (rows_moved && idx != j) vdst[u] = j;
                     } else {
                         pw[u] = 0.f;
                         vv[u] = Vec16{0u, 0u, 0u, 0u};
@@ -881,7 +916,13 @@ swa_decode_kernel(DecodeArgs a)
 #pragma unroll
                     for (int e = 0; e < EPV; ++e) acc[e] = __builtin_fmaf(pw[u], f[e], acc[e]);
                     ps += pw[u];
+                    if (vdst[u] >= 0) store16(Vp + (int64_t)vdst[u] * ROWB + sub * 16, vv[u]);
                 }
+            }
+            if (rows_moved) {
+#pragma unroll
+                for (int u = 0; u < UM; ++u)
+                    if (kdst[u] >= 0) store16(Kp + (int64_t)kdst[u] * ROWB + sub * 16, kmv[u]);
             }
 #pragma unroll
             for (int o = LPR; o < kWave; o <<= 1) {
@@ -954,18 +995,32 @@ swa_decode_kernel(DecodeArgs a)
                         }
                     }
                 } else {
-                    for (int k = grp; k < n_moves; k += NG) {
-                        int src = s_movers[k], dst = s_holes[k];
-                        src = src > len ? len : src;
-                        dst = dst >= keep ? keep - 1 : dst;
-                        Vec16 kr = load16(Kp + (int64_t)src * ROWB + sub * 16);
-                        Vec16 vr = load16(Vp + (int64_t)src * ROWB + sub * 16);
-                        if (src == len) {
-                            kr = nk;
-                            vr = nv;
+                    // UM rows per group in flight at a time, key rows and value rows in turn: a
+                    // batch's loads are all issued before its first store.  After a gathered output
+                    // pass only the key rows beyond its first batch are left.
+                    for (int k0 = rows_moved ? NG * UM : 0; k0 < n_moves; k0 += NG * UM) {
+#pragma unroll
+                        for (int t = 0; t < (rows_moved ? 1 : 2); ++t) {
+                            char* base = t == 0 ? Kp : Vp;
+                            Vec16 rr[UM];
+                            int dd[UM];
+#pragma unroll
+                            for (int u = 0; u < UM; ++u) {
+                                const int k = k0 + u * NG + grp;
+                                dd[u] = -1;
+                                if (k < n_moves) {
+                                    int src = s_movers[k], dst = s_holes[k];
+                                    src = src > len ? len : src;
+                                    dst = dst >= keep ? keep - 1 : dst;
+                                    rr[u] = load16(base + (int64_t)src * ROWB + sub * 16);
+                                    if (src == len) rr[u] = t == 0 ? nk : nv;
+                                    dd[u] = dst;
+                                }
+                            }
+#pragma unroll
+                            for (int u = 0; u < UM; ++u)
+                                if (dd[u] >= 0) store16(base + (int64_t)dd[u] * ROWB + sub * 16, rr[u]);
                         }
-                        store16(Kp + (int64_t)dst * ROWB + sub * 16, kr);
-                        store16(Vp + (int64_t)dst * ROWB + sub * 16, vr);
                     }
                 }
             } else {
@@ -1024,9 +1079,10 @@ swa_decode_kernel(DecodeArgs a)
     if (fc) {
         // The new length is published through kept_cnt (every head writes the same value);
         // cache_len is only read, so no workgroup can observe a half-updated step.
+        // (every head of a sequence computes the same value: head 0 writes it)
         if (tid == 0) {
             if (overflow) atomicOr(a.status, kStatusCapacityBit);
-            a.kept_cnt[s] = overflow ? len : keep;
+            if (pair - (int64_t)s * a.h == 0) a.kept_cnt[s] = overflow ? len : keep;
         }
         return;
     }
