@@ -496,9 +496,11 @@ def main():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     ap.add_argument("--others", default="c5_llama7b_sp50,c5_llama7b_sp90,c4_opt30b,c3_opt13b,c2_opt6p7b",
-                    help="comma list of further workloads summarised in the same line ('' = none)")
+                    help="comma list of further workloads summarised in the same line ('none' = none)")
+    ap.add_argument("--no-whole-trajectory", action="store_true",
+                    help="with --steps: do not also time whole trajectories of the headline workload")
     ap.add_argument("--ordered-forms", default="fused,split",
-                    help="further step forms timed beside --step-mode for every workload ('' = none)")
+                    help="further step forms timed beside --step-mode for every workload ('none' = none)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus must be 1 "
@@ -520,7 +522,8 @@ def main():
     if args.compact_every != 1 and args.step_mode != "split":
         print("bench.py: --compact-every needs --step-mode split (the fused forms compact every step)", file=sys.stderr)
         sys.exit(2)
-    extra_forms = [x for x in args.ordered_forms.split(",") if x and x != args.step_mode]
+    none = ("", "none")
+    extra_forms = [x for x in args.ordered_forms.split(",") if x not in none and x != args.step_mode]
     if args.compact_every != 1 or args.step_mode in ("shared", "window"):
         extra_forms = []
     res = bench_workload(wl, args.steps, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
@@ -570,6 +573,13 @@ def main():
     if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
 
+    # --steps covers only the first steps of the trajectory (the step after the prompt weighs 1/replicas
+    # of them): the same workload over whole trajectories, for reference
+    if args.steps is not None and not args.no_whole_trajectory and res["steps"] < wl.steps * res["replicas"]:
+        r = bench_workload(wl, None, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
+                           kv_int8=args.kv_int8, compact_every=args.compact_every)
+        line["whole_trajectory"] = summary_of(r, args.step_mode, args.kv_int8, wl.name)
+
     # the same workload in the forms that keep the cache in token order
     forms = []
     for sm in extra_forms:
@@ -582,7 +592,7 @@ def main():
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)
 
     others = []
-    for name in [x for x in args.others.split(",") if x and x != args.config]:
+    for name in [x for x in args.others.split(",") if x not in none and x != args.config]:
         o = W.CONFIGS[name]
         if args.kv_int8 and o.dtype != "f16":
             continue
