@@ -302,8 +302,11 @@ int swa_prefill_rows(const swa_params *params, const void *q_tail, int32_t R, co
                      const int32_t *cache_len, float *ring, void *workspace, void *stream);
 
 /*
- * swa_decode_step with the strict local attention sum.  params->flags must be exactly
- * SWA_FUSE_COMPACTION | SWA_UNORDERED.  Differences from swa_decode_step in that form:
+ * swa_decode_step with the strict local attention sum.  params->flags must contain
+ * SWA_FUSE_COMPACTION | SWA_UNORDERED (the ring's columns follow their tokens through the
+ * hole-filling compaction only) and may add SWA_HEAD_SHARED: the selection key is then the sum
+ * over the heads of the per-head window sums (Algorithm 1's header note together with its
+ * line 2), with the larger workspace of that flag.  Differences from swa_decode_step:
  *   3'. importance: ring row `ring_row` (0 <= ring_row < R) is replaced by this step's weights p,
  *       and score[i] = sum over the R ring rows at slot i, added in row order in fp32; the token
  *       appended in this step has no earlier rows.  score is output only (the old content is
@@ -316,6 +319,19 @@ int swa_decode_step_window(const swa_params *params, const void *q, const void *
                            int32_t ring_row, float *score, int32_t *pos, int32_t *cache_len,
                            const int32_t *seq_len, int32_t *kept_idx, int32_t *kept_cnt, void *out,
                            float *probs_dbg, void *workspace, void *stream);
+
+/*
+ * swa_decode_step_window over a compressed cache (Section V-B together with Algorithm 1 line 2):
+ * arguments as swa_decode_step_q8 (k_codes, v_codes, qparams; flags contain SWA_KV_INT8) plus the
+ * ring arguments of swa_decode_step_window.  The ring at the end of the prompt comes from
+ * swa_prefill_rows on the fp16 cache, before swa_quantize_kv compresses it.
+ */
+int swa_decode_step_window_q8(const swa_params *params, const void *q, const void *k_new,
+                              const void *v_new, void *k_codes, void *v_codes, const float *qparams,
+                              float *ring, int32_t R, int32_t ring_row, float *score, int32_t *pos,
+                              int32_t *cache_len, const int32_t *seq_len, int32_t *kept_idx,
+                              int32_t *kept_cnt, void *out, float *probs_dbg, void *workspace,
+                              void *stream);
 
 /*
  * Prefill: dense causal attention over the whole prompt (Eq. 1-2 with the causal mask) plus the

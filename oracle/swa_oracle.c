@@ -609,19 +609,24 @@ int swa_oracle_compact_ring(int32_t b, int32_t h, int32_t cap, int32_t R, double
 }
 
 /* One decode step with the strict local attention sum: as swa_oracle_decode_step, with the    */
-/* importance taken from the ring instead of the running sum.                                  */
+/* importance taken from the ring instead of the running sum.  head_shared: the selection key  */
+/* is that importance summed over the heads (the note in Algorithm 1's header applied to the   */
+/* sum of its line 2), one token set per sequence.                                             */
 int swa_oracle_decode_step_window(int32_t b, int32_t h, int32_t d, int32_t cap, int32_t w,
                                   int32_t sparsity_bp, double scale, int32_t R, int32_t row,
                                   const double *q, const double *k_new, const double *v_new,
                                   double *K, double *V, double *ring, double *score, int32_t *pos,
                                   int32_t *cache_len, const int32_t *seq_len,
-                                  int32_t *kept_idx, int32_t *kept_cnt, double *out, double *probs)
+                                  int32_t *kept_idx, int32_t *kept_cnt, double *out, double *probs,
+                                  int32_t head_shared)
 {
     int rc = swa_oracle_append(b, h, d, cap, k_new, v_new, K, V, score, pos, cache_len, seq_len);
     if (rc) return rc;
     swa_oracle_probs(b, h, d, cap, scale, q, K, cache_len, probs);
     swa_oracle_window_accumulate(b, h, cap, R, row, probs, cache_len, ring, score);
-    rc = swa_oracle_select(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt);
+    rc = head_shared
+             ? swa_oracle_select_shared(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt)
+             : swa_oracle_select(b, h, cap, w, sparsity_bp, score, cache_len, seq_len, kept_idx, kept_cnt);
     if (rc) return rc;
     return swa_oracle_sparse_attention(b, h, d, cap, scale, q, K, V, kept_idx, kept_cnt, out);
 }

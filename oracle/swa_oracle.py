@@ -244,7 +244,7 @@ def compact_ring(ring, kept_idx, kept_cnt) -> None:
 
 
 def decode_step_window(q, k_new, v_new, K, V, ring, row: int, score, pos, cache_len, seq_len, w: int,
-                       sparsity_bp: int, scale: float):
+                       sparsity_bp: int, scale: float, head_shared: bool = False):
     """One step with the strict local attention sum.  In place: K, V, ring, score, pos, cache_len.
 
     Returns (kept_idx, kept_cnt, out, probs).
@@ -259,7 +259,7 @@ def decode_step_window(q, k_new, v_new, K, V, ring, row: int, score, pos, cache_
         b, h, d, cap, ctypes.c_int32(w), ctypes.c_int32(sparsity_bp), ctypes.c_double(scale),
         ctypes.c_int32(R), ctypes.c_int32(row), _pd(_f64(q)), _pd(_f64(k_new)), _pd(_f64(v_new)),
         _pd(K), _pd(V), _pd(ring), _pd(score), _pi(pos), _pi(cache_len), _pi(_i32(seq_len)),
-        _pi(kept_idx), _pi(kept_cnt), _pd(out), _pd(p))
+        _pi(kept_idx), _pi(kept_cnt), _pd(out), _pd(p), ctypes.c_int32(1 if head_shared else 0))
     _check(rc, "decode_step_window")
     return kept_idx, kept_cnt, out, p
 

@@ -36,7 +36,7 @@ DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SW
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
            "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read",
-           "swa_prepare", "swa_decode_step_static"]
+           "swa_prepare", "swa_decode_step_static", "swa_decode_step_window_q8"]
 
 
 class SwaParams(ctypes.Structure):
@@ -94,6 +94,8 @@ def lib():
         L.swa_prefill_rows.argtypes = [pp, vp, ctypes.c_int32, vp, i32p, vp, vp, vp]
         L.swa_decode_step_window.restype = ctypes.c_int
         L.swa_decode_step_window.argtypes = [pp] + [vp] * 6 + [ctypes.c_int32] * 2 + [vp] * 10
+        L.swa_decode_step_window_q8.restype = ctypes.c_int
+        L.swa_decode_step_window_q8.argtypes = [pp] + [vp] * 7 + [ctypes.c_int32] * 2 + [vp] * 10
         L.swa_prefill_attention.restype = ctypes.c_int
         L.swa_prefill_attention.argtypes = [pp, vp, vp, vp, i32p, vp, ctypes.c_int32, vp, vp, vp]
         L.swa_probe_stream_read.restype = ctypes.c_int
@@ -216,6 +218,17 @@ def swa_decode_step_window(params: SwaParams, q, k_new, v_new, k_cache, v_cache,
                                         _ptr(seq_len), _ptr(kept_idx), _ptr(kept_cnt), _ptr(out),
                                         _ptr(probs_dbg), _ptr(workspace), _stream(stream)),
            "swa_decode_step_window")
+
+
+def swa_decode_step_window_q8(params: SwaParams, q, k_new, v_new, k_codes, v_codes, qparams, ring, R: int,
+                              ring_row: int, score, pos, cache_len, seq_len, kept_idx, kept_cnt, out,
+                              probs_dbg, workspace, stream=None) -> None:
+    _check(lib().swa_decode_step_window_q8(ctypes.byref(params), _ptr(q), _ptr(k_new), _ptr(v_new),
+                                           _ptr(k_codes), _ptr(v_codes), _ptr(qparams), _ptr(ring), int(R),
+                                           int(ring_row), _ptr(score), _ptr(pos), _ptr(cache_len),
+                                           _ptr(seq_len), _ptr(kept_idx), _ptr(kept_cnt), _ptr(out),
+                                           _ptr(probs_dbg), _ptr(workspace), _stream(stream)),
+           "swa_decode_step_window_q8")
 
 
 def swa_prefill_attention(params: SwaParams, q, k_cache, v_cache, cache_len, out, R: int, score,

@@ -300,6 +300,21 @@ int swa_prefill_attention(const swa_params* params, const void* q, const void* k
     return swa::launch_prefill(*params, swa::effective_scale(params), q, R, k_cache, cache_len, score, nullptr, true, st);
 }
 
+static int window_common(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                         void* k_cache, void* v_cache, const float* qparams, float* ring, int32_t R,
+                         int32_t ring_row, float* score, int32_t* pos, int32_t* cache_len, const int32_t* seq_len,
+                         int32_t* kept_idx, int32_t* kept_cnt, void* out, float* probs_dbg, void* workspace,
+                         void* stream)
+{
+    // the ring's columns follow their tokens through the hole-filling compaction only
+    const int32_t form = params->flags & ~(SWA_HEAD_SHARED | SWA_KV_INT8);
+    if (form != (SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
+    if (!ring) return SWA_ERR_NULL;
+    if (R < 1 || R > SWA_MAX_WINDOW_ROWS || ring_row < 0 || ring_row >= R) return SWA_ERR_BAD_SHAPE;
+    return decode_common(params, q, k_new, v_new, k_cache, v_cache, qparams, score, pos, cache_len, seq_len,
+                         kept_idx, kept_cnt, out, probs_dbg, workspace, stream, ring, R, ring_row);
+}
+
 int swa_decode_step_window(const swa_params* params, const void* q, const void* k_new, const void* v_new,
                            void* k_cache, void* v_cache, float* ring, int32_t R, int32_t ring_row, float* score,
                            int32_t* pos, int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx,
@@ -307,11 +322,23 @@ int swa_decode_step_window(const swa_params* params, const void* q, const void* 
 {
     int rc = swa::validate(params);
     if (rc != SWA_OK) return rc;
-    if (params->flags != (SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
-    if (!ring) return SWA_ERR_NULL;
-    if (R < 1 || R > SWA_MAX_WINDOW_ROWS || ring_row < 0 || ring_row >= R) return SWA_ERR_BAD_SHAPE;
-    return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
-                         kept_idx, kept_cnt, out, probs_dbg, workspace, stream, ring, R, ring_row);
+    if (params->flags & SWA_KV_INT8) return SWA_ERR_UNSUPPORTED_DTYPE;   // codes need their parameters
+    return window_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, ring, R, ring_row, score, pos,
+                         cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+int swa_decode_step_window_q8(const swa_params* params, const void* q, const void* k_new, const void* v_new,
+                              void* k_codes, void* v_codes, const float* qparams, float* ring, int32_t R,
+                              int32_t ring_row, float* score, int32_t* pos, int32_t* cache_len,
+                              const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt, void* out,
+                              float* probs_dbg, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!(params->flags & SWA_KV_INT8)) return SWA_ERR_UNSUPPORTED_DTYPE;
+    if (!qparams) return SWA_ERR_NULL;
+    return window_common(params, q, k_new, v_new, k_codes, v_codes, qparams, ring, R, ring_row, score, pos,
+                         cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
 }
 
 int swa_decode_step(const swa_params* params, const void* q, const void* k_new, const void* v_new,

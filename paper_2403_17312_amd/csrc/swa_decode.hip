@@ -443,7 +443,8 @@ swa_decode_kernel(DecodeArgs a)
         // further slots of long caches, are read in the accumulation loop itself).
         constexpr int kRingAhead = 32;
         float* Rg = has_ring ? a.ring + pair * (int64_t)a.ring_rows * cap : nullptr;
-        const bool ring_ahead = has_ring && a.ring_rows <= kRingAhead;
+        // (not on the 8-bit cache, whose lanes have no registers to spare for it)
+        const bool ring_ahead = has_ring && !kQ8 && a.ring_rows <= kRingAhead;
         float rpre[kRingAhead];
         if (ring_ahead) {
             const bool old = tid < len;
@@ -1142,13 +1143,11 @@ static int launch_decode_nt(const DecodeArgs& a, int64_t pairs, size_t lds_bytes
 template <typename T, int D>
 static int launch_decode_t(const DecodeArgs& a, int64_t pairs, size_t lds_bytes, int nt, hipStream_t stream)
 {
-    if constexpr (Elem<T>::kBytes != 1) {     // the strict window is not offered on the 8-bit cache
-        if (a.ring) {
-            switch (nt) {
-                case 128: return launch_decode_nt<T, D, 128, true>(a, pairs, lds_bytes, stream);
-                case 256: return launch_decode_nt<T, D, 256, true>(a, pairs, lds_bytes, stream);
-                default: return launch_decode_nt<T, D, 512, true>(a, pairs, lds_bytes, stream);
-            }
+    if (a.ring) {
+        switch (nt) {
+            case 128: return launch_decode_nt<T, D, 128, true>(a, pairs, lds_bytes, stream);
+            case 256: return launch_decode_nt<T, D, 256, true>(a, pairs, lds_bytes, stream);
+            default: return launch_decode_nt<T, D, 512, true>(a, pairs, lds_bytes, stream);
         }
     }
     switch (nt) {
@@ -1187,11 +1186,9 @@ static int prepare_t()
     int rc = prepare_one<T, D, 128, false>();
     if (rc == SWA_OK) rc = prepare_one<T, D, 256, false>();
     if (rc == SWA_OK) rc = prepare_one<T, D, 512, false>();
-    if constexpr (Elem<T>::kBytes != 1) {
-        if (rc == SWA_OK) rc = prepare_one<T, D, 128, true>();
-        if (rc == SWA_OK) rc = prepare_one<T, D, 256, true>();
-        if (rc == SWA_OK) rc = prepare_one<T, D, 512, true>();
-    }
+    if (rc == SWA_OK) rc = prepare_one<T, D, 128, true>();
+    if (rc == SWA_OK) rc = prepare_one<T, D, 256, true>();
+    if (rc == SWA_OK) rc = prepare_one<T, D, 512, true>();
     return rc;
 }
 

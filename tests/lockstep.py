@@ -398,7 +398,7 @@ def run_every_pair(wl: W.Workload, steps: int, chunk: int, device="cuda", first_
 def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[int] = None,
                         seqs: Optional[Sequence[int]] = None, heads: Optional[Sequence[int]] = None,
                         slack: str = "nan", use_len_bound: bool = False, seed_rows: bool = True,
-                        sparsity_of_step=None) -> Report:
+                        sparsity_of_step=None, head_shared: bool = False, kv_int8: bool = False) -> Report:
     """Lock-step parity of swa_decode_step_window (strict local attention sum over a ring of R rows,
     unordered fused compaction) against the oracle's *_window routines.  The oracle's ring is the
     GPU's fp32 ring in token order (adopted row by row), so after every compaction the two rings
@@ -410,6 +410,12 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
     prompt = W.make_prompt(wl, device, slack=slack)
     st = new_state(wl, prompt)
     st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+    if head_shared:
+        # one token set per sequence from the head-summed window sums: every head is needed
+        assert len(heads) == wl.h
+        st.params.flags |= B.SWA_HEAD_SHARED
+        st.workspace = torch.zeros((B.swa_workspace_bytes(st.params),), dtype=torch.uint8, device=device)
+        B.swa_workspace_init(st.params, st.workspace)
     rep = Report(pairs=len(seqs) * len(heads))
     seqs_t = torch.tensor(seqs, device=device)
     heads_t = torch.tensor(heads, device=device)
@@ -437,6 +443,27 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
     for s_i, L in enumerate(prompt["lengths"]):
         ring[s_i, :, :, L:] = float("nan")
     st.score.fill_(float("nan"))            # output only in this mode
+    qp = None
+    if kv_int8:
+        # Section V-B after the prompt's rows are in the ring: parameters and codes bit-exact, then the
+        # oracle's cache holds the de-quantised values
+        st.quantize()
+        qp_g = [_sub(st.qparams[k], seqs_t, heads_t).cpu().numpy() for k in range(4)]
+        lamK, zK = O.kv_qparams(np.nan_to_num(K_o), len_o)
+        lamV, zV = O.kv_qparams(np.nan_to_num(V_o), len_o)
+        for g, o in zip(qp_g, (lamK, zK, lamV, zV)):
+            assert np.array_equal(g, o), "quantisation parameters"
+        cK, cV = O.kv_quantize(np.nan_to_num(K_o), len_o, lamK, zK), O.kv_quantize(np.nan_to_num(V_o), len_o, lamV, zV)
+        cK_g = _sub(st.K, seqs_t, heads_t).cpu().numpy()
+        for i, L in enumerate(len_o):
+            assert np.array_equal(cK_g[i, :, :L], cK[i, :, :L]), "key codes"
+        K_o, V_o = O.kv_dequantize(cK, len_o, lamK, zK), O.kv_dequantize(cV, len_o, lamV, zV)
+        qp = (lamK, zK, lamV, zV)
+        ones = np.ones_like(len_o)
+
+        def through_codes(x, lam, zero):
+            x4 = np.ascontiguousarray(x[:, :, None, :])
+            return O.kv_dequantize(O.kv_quantize(x4, ones, lam, zero), ones, lam, zero)[:, :, 0, :]
 
     host_len = list(prompt["lengths"])
     for t in range(steps):
@@ -450,16 +477,24 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
             st.params.len_bound = max(host_len) + 1
         ring_prev = _sub(ring, seqs_t, heads_t).cpu().numpy()
         pos_prev = _sub(st.pos, seqs_t, heads_t).cpu().numpy().copy()
-        B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, R, row, st.score, st.pos,
-                                 st.cache_len, st.seq_len, st.kept_idx, st.kept_cnt, st.out, st.probs,
-                                 st.workspace)
+        if kv_int8:
+            B.swa_decode_step_window_q8(st.params, q, kn, vn, st.K, st.V, st.qparams, ring, R, row, st.score,
+                                        st.pos, st.cache_len, st.seq_len, st.kept_idx, st.kept_cnt, st.out,
+                                        st.probs, st.workspace)
+        else:
+            B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, R, row, st.score, st.pos,
+                                     st.cache_len, st.seq_len, st.kept_idx, st.kept_cnt, st.out, st.probs,
+                                     st.workspace)
         st.cache_len, st.kept_cnt = st.kept_cnt, st.cache_len
         for s_i in range(wl.b):
             host_len[s_i] = B.swa_budget(prompt["lengths"][s_i] + t + 1, host_len[s_i] + 1, wl.w, sp_t)[0]
 
         q_o, kn_o, vn_o = (_np64(_sub(x, seqs_t, heads_t)) for x in (q, kn, vn))
+        if kv_int8:
+            kn_o, vn_o = through_codes(kn_o, qp[0], qp[1]), through_codes(vn_o, qp[2], qp[3])
         kept_o, cnt_o, out_o, p_o = O.decode_step_window(q_o, kn_o, vn_o, K_o, V_o, ring_o, row, score_o,
-                                                         pos_o, len_o, n_o, wl.w, sp_t, wl.scale)
+                                                         pos_o, len_o, n_o, wl.w, sp_t, wl.scale,
+                                                         head_shared=head_shared)
         kept_g = _sub(st.kept_idx, seqs_t, heads_t).cpu().numpy()
         cnt_g = st.cache_len[seqs_t].cpu().numpy()
         assert np.array_equal(cnt_g, cnt_o), f"step {t}: kept_cnt {cnt_g} vs {cnt_o}"
@@ -508,7 +543,15 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
             assert np.all(se <= 1e-5 * np.abs(score_o[i, :, :m]) + 1e-12), f"step {t}: window sum"
             rep.max_prob_rel = max(rep.max_prob_rel, float(np.max(pe / (np.abs(p_o[i, :, :m]) + 1e-30))))
             rep.max_score_rel = max(rep.max_score_rel, float(np.max(se / (np.abs(score_o[i, :, :m]) + 1e-30))))
-        kept_ref, cnt_ref = O.select(S_g, len_o, n_o, wl.w, sp_t)
+        if head_shared:
+            # the kernel sums the heads in fp32, head 0 first: take the decision in that precision
+            tot32 = np.zeros((S_g.shape[0], S_g.shape[2]), dtype=np.float32)
+            for hd in range(len(heads)):
+                tot32 = (tot32 + S_can[:, hd]).astype(np.float32)
+            k1, cnt_ref = O.select(tot32[:, None, :].astype(np.float64), len_o, n_o, wl.w, sp_t)
+            kept_ref = np.repeat(k1, len(heads), axis=1)
+        else:
+            kept_ref, cnt_ref = O.select(S_g, len_o, n_o, wl.w, sp_t)
         assert np.array_equal(cnt_ref, cnt_g)
         for i, c in enumerate(cnt_g):
             assert np.array_equal(kept_can[i, :, :c], kept_ref[i, :, :c]), \
@@ -518,9 +561,10 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
                 if diff:
                     m = len_o[i]
                     nl = O.budget(int(n_o[i]), int(m), wl.w, sp_t)[1]
-                    cutoff = np.sort(score_o[i, hd, :m - nl])[::-1][c - nl - 1]
+                    sel_o = score_o[i].sum(axis=0) if head_shared else score_o[i, hd]
+                    cutoff = np.sort(sel_o[:m - nl])[::-1][c - nl - 1]
                     for j in diff:
-                        assert abs(score_o[i, hd, j] - cutoff) <= 2e-5 * abs(cutoff), f"step {t}: not a near tie"
+                        assert abs(sel_o[j] - cutoff) <= 2e-5 * abs(cutoff), f"step {t}: not a near tie"
                     rep.near_tie_flips += len(diff) // 2
             rep.evictions += (int(len_o[i]) - int(c)) * len(heads)
         out_ref = O.sparse_attention(q_o, K_o, V_o, kept_can, cnt_g, wl.scale)
@@ -533,8 +577,13 @@ def run_lockstep_window(wl: W.Workload, R: int, device="cuda", steps: Optional[i
         score_o = S_g.copy()
         O.compact_ring(ring_o, kept_can, cnt_g)
         O.compact(K_o, V_o, score_o, pos_o, kept_can, cnt_g, len_o)
-        K_g = _np64(_sub(st.K, seqs_t, heads_t))
-        V_g = _np64(_sub(st.V, seqs_t, heads_t))
+        if kv_int8:
+            capc = np.full_like(len_o, st.K.shape[2])
+            K_g = O.kv_dequantize(_sub(st.K, seqs_t, heads_t).cpu().numpy(), capc, qp[0], qp[1])
+            V_g = O.kv_dequantize(_sub(st.V, seqs_t, heads_t).cpu().numpy(), capc, qp[2], qp[3])
+        else:
+            K_g = _np64(_sub(st.K, seqs_t, heads_t))
+            V_g = _np64(_sub(st.V, seqs_t, heads_t))
         for (i, hd), o2 in orders.items():
             L = len_o[i]
             assert np.array_equal(K_g[i, hd, o2], K_o[i, hd, :L]), f"step {t}: K after compaction"

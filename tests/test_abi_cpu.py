@@ -174,7 +174,20 @@ def test_strict_window_entry_points_validate_their_arguments(B):
         return L.swa_decode_step_window(ctypes.byref(p), ok, ok, ok, ok, ok, ring, R, row, ok, ok, cache_len,
                                         ok, ok, ok, ok, ok, ok, ok)
     assert step(p0) == B.SWA_ERR_BAD_SHAPE                      # only the unordered fused form
-    assert step(B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=7)) == B.SWA_ERR_BAD_SHAPE
+    assert step(B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=B.SWA_FUSE_COMPACTION)) == B.SWA_ERR_BAD_SHAPE
+    # codes need their parameters: the plain call refuses a compressed cache, the q8 call a plain one
+    pq = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=pu.flags | B.SWA_KV_INT8)
+    assert step(pq) == B.SWA_ERR_UNSUPPORTED_DTYPE
+
+    def step_q8(p, qparams=ok, ring=ok, R=4, row=0):
+        return L.swa_decode_step_window_q8(ctypes.byref(p), ok, ok, ok, ok, ok, qparams, ring, R, row, ok, ok,
+                                           ctypes.c_void_p(0x2000), ok, ok, ok, ok, ok, ok, ok)
+    assert step_q8(pu) == B.SWA_ERR_UNSUPPORTED_DTYPE
+    assert step_q8(pq, qparams=None) == B.SWA_ERR_NULL
+    assert step_q8(pq, ring=None) == B.SWA_ERR_NULL
+    assert step_q8(pq, R=4, row=4) == B.SWA_ERR_BAD_SHAPE
+    assert step_q8(B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16, flags=B.SWA_FUSE_COMPACTION | B.SWA_KV_INT8)) \
+        == B.SWA_ERR_BAD_SHAPE
     assert step(pu, ring=None) == B.SWA_ERR_NULL
     assert step(pu, R=0) == B.SWA_ERR_BAD_SHAPE
     assert step(pu, R=B.SWA_MAX_WINDOW_ROWS + 1) == B.SWA_ERR_BAD_SHAPE

@@ -265,6 +265,31 @@ def test_strict_window_sum_matches_the_oracle(env):
     assert rep.steps == 32
 
 
+def test_strict_window_on_the_compressed_cache_and_with_the_head_reduced_set(env):
+    # Algorithm 1 line 2 (the ring of attention rows) combined with Section V-B (8-bit cache) and with
+    # the note in Algorithm 1's header (importance summed over the heads), and all three together
+    O, B, W, LS = env
+    for dtype, d, R, w, q8, sh in [("f16", 128, 6, 5, True, False), ("f16", 64, 3, 0, True, False),
+                                   ("f16", 128, 5, 4, False, True), ("bf16", 64, 4, 7, False, True),
+                                   ("f32", 128, 2, B.SWA_W_EVEN_SPLIT, False, True), ("f16", 128, 7, 3, True, True)]:
+        wl = W.Workload(f"t_winx_{dtype}_{R}", 47, b=3, h=4, d=d, dtype=dtype, prompt_lo=2, prompt_hi=260,
+                        steps=2 * R + 6, w=w, sparsity_bp=7000, hh_frac=0.02)
+        _say(f"  window x {'int8 ' if q8 else ''}{'head-shared ' if sh else ''}{dtype} d={d} R={R}")
+        rep = LS.run_lockstep_window(wl, R, kv_int8=q8, head_shared=sh)
+        assert rep.evictions > 0
+    # a budget that tightens and relaxes, all three combined
+    wl = W.Workload("t_winx_sched", 48, b=2, h=4, d=128, dtype="f16", prompt_lo=60, prompt_hi=90,
+                    steps=24, w=4, sparsity_bp=3000, hh_frac=0.02)
+    LS.run_lockstep_window(wl, 6, kv_int8=True, head_shared=True,
+                           sparsity_of_step=lambda t: 3000 if t < 10 else (8500 if t < 12 else 6000))
+    _say("  config 2 at full size, every pair: window x int8, window x head-shared")
+    rep = LS.run_lockstep_window(W.CONFIGS["c2_opt6p7b"], 16, use_len_bound=True, kv_int8=True)
+    assert rep.steps == 32
+    rep = LS.run_lockstep_window(W.CONFIGS["c2_opt6p7b"], 16, use_len_bound=True, head_shared=True)
+    _say(f"  {rep}")
+    assert rep.steps == 32
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]

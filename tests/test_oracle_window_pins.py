@@ -177,3 +177,55 @@ def test_prefill_attention_is_causal_dense_attention(oracle):
     out2 = O.prefill_attention(Q2, K2, V2, lens, 0.45)
     assert np.array_equal(out2[:, :, :5], out[:, :, :5])
     assert not np.allclose(out2[0, :, 5:19], out[0, :, 5:19])
+
+
+def test_window_step_with_the_head_reduced_token_set(oracle):
+    # Algorithm 1's header note on top of its line 2: the window sums of the heads are added and every
+    # head of a sequence keeps the same tokens.  Pinned against the separately pinned pieces: the
+    # window sums of the per-head step, summed over the heads with numpy, ranked by brute force.
+    O = oracle
+    rng = np.random.default_rng(23)
+    b, h, cap, d, R, w, sp = 2, 3, 40, 5, 3, 2, 5000
+    K, V, pos, lens = _state(rng, b, h, cap, d, [21, 12])
+    ring = np.zeros((b, h, R, cap))
+    ring[:, :, :R] = O.prefill_rows(rng.standard_normal((b, h, R, d)), K, lens, 0.5)
+    A = dict(K=K.copy(), V=V.copy(), pos=pos.copy(), len=lens.copy(), score=np.zeros((b, h, cap)), ring=ring.copy())
+    Bs = dict(K=K.copy(), V=V.copy(), pos=pos.copy(), len=lens.copy(), score=np.zeros((b, h, cap)), ring=ring.copy())
+    n = lens.copy()
+    for t in range(6):
+        n = n + 1
+        q, kn, vn = (rng.standard_normal((b, h, d)) for _ in range(3))
+        # per-head step on a copy: gives the window sums (they do not depend on the selection)
+        tmp = {k: v.copy() for k, v in A.items()}
+        O.decode_step_window(q, kn, vn, tmp["K"], tmp["V"], tmp["ring"], t % R, tmp["score"], tmp["pos"], tmp["len"],
+                             n, w, sp, 0.5)
+        kept, cnt, out, p = O.decode_step_window(q, kn, vn, Bs["K"], Bs["V"], Bs["ring"], t % R, Bs["score"],
+                                                 Bs["pos"], Bs["len"], n, w, sp, 0.5, head_shared=True)
+        np.testing.assert_array_equal(Bs["score"], tmp["score"])
+        for s in range(b):
+            m = Bs["len"][s]
+            keep, nl, ng = O.budget(int(n[s]), int(m), w, sp)
+            assert cnt[s] == keep
+            tot = Bs["score"][s].sum(axis=0)[:m - nl]
+            order = sorted(range(m - nl), key=lambda i: (-tot[i], i))[:ng]
+            want = sorted(order) + list(range(m - nl, m))
+            for hd in range(h):
+                assert kept[s, hd, :keep].tolist() == want
+            # the output is the renormalised attention over that set
+            for hd in range(h):
+                z = Bs["K"][s, hd, want] @ q[s, hd] * 0.5
+                np.testing.assert_allclose(out[s, hd], softmax(z) @ Bs["V"][s, hd, want], rtol=1e-10, atol=1e-12)
+        O.compact_ring(Bs["ring"], kept, cnt)
+        O.compact(Bs["K"], Bs["V"], Bs["score"], Bs["pos"], kept, cnt, Bs["len"])
+        # keep the per-head reference state in step with the shared one
+        A = {k: v.copy() for k, v in Bs.items()}
+    # a single head: the shared rule is the per-head rule
+    K1, V1, pos1, lens1 = _state(rng, 1, 1, 30, 4, [15])
+    r1 = np.zeros((1, 1, 2, 30))
+    q, kn, vn = (rng.standard_normal((1, 1, 4)) for _ in range(3))
+    a = O.decode_step_window(q, kn, vn, K1.copy(), V1.copy(), r1.copy(), 0, np.zeros((1, 1, 30)), pos1.copy(),
+                             lens1.copy(), lens1 + 1, 3, 6000, 0.5)
+    b_ = O.decode_step_window(q, kn, vn, K1.copy(), V1.copy(), r1.copy(), 0, np.zeros((1, 1, 30)), pos1.copy(),
+                              lens1.copy(), lens1 + 1, 3, 6000, 0.5, head_shared=True)
+    np.testing.assert_array_equal(a[0], b_[0])
+    np.testing.assert_array_equal(a[2], b_[2])
