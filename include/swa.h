@@ -58,7 +58,9 @@ typedef enum {
     SWA_ERR_BAD_SPARSITY = -5,      /* sparsity_bp outside 0..9999 */
     SWA_ERR_CAPACITY = -6,          /* cap above SWA_MAX_CAP, or (status) a cache was full */
     SWA_ERR_HIP = -7,               /* a HIP runtime call failed */
-    SWA_ERR_ALIGNMENT = -8          /* a row pointer is not 16-byte aligned */
+    SWA_ERR_ALIGNMENT = -8,         /* a row pointer is not 16-byte aligned */
+    SWA_ERR_HOST_STORE_FULL = -9,   /* (status) a pair's host store had no room for its evicted tokens */
+    SWA_ERR_BAD_REQUEST = -10       /* (status) a reload named a token that the host store does not hold */
 } swa_status;
 
 typedef struct {
@@ -155,7 +157,8 @@ size_t swa_workspace_bytes(const swa_params *params);
 int swa_workspace_init(const swa_params *params, void *workspace, void *stream);
 
 /* Synchronises `stream`, copies the sticky status bits to the host and clears them.
- * *status_out = SWA_OK or SWA_ERR_CAPACITY (some decode step met a full cache).
+ * *status_out = SWA_OK, SWA_ERR_CAPACITY (some step met a full cache), SWA_ERR_HOST_STORE_FULL or
+ * SWA_ERR_BAD_REQUEST (offload tier), the first of these that applies.
  * workspace == NULL reads the status word of swa_decode_step_static on the current device.
  * This is the only entry point that blocks. */
 int swa_check_status(const swa_params *params, void *workspace, void *stream, int32_t *status_out);
@@ -348,6 +351,60 @@ int swa_decode_step_window_q8(const swa_params *params, const void *q, const voi
 int swa_prefill_attention(const swa_params *params, const void *q, const void *k_cache,
                           const void *v_cache, const int32_t *cache_len, void *out, int32_t R,
                           float *score, void *workspace, void *stream);
+
+/*
+ * Token-level offload tier: the store and load halves of the GPU-CPU caching phase of the
+ * paper's dynamic scheduling (Section V-A, Algorithm 2, Phase II: tokens that leave GPU memory are
+ * stored in CPU memory, tokens needed again are loaded back; KV tensors are managed per token, not
+ * per head).  When to offload and what to load back is the scheduler's policy and not part of this
+ * library; recomputation (Phase III) needs the model and is out of scope.
+ *
+ * The host store of one layer, owned by the caller:
+ *   k, v    [b, h, host_cap, d]  PINNED host memory that the device can address (hipHostMalloc,
+ *                                 or a framework's pinned allocation), element type of the cache
+ *                                 (8-bit codes with SWA_KV_INT8);
+ *   score   [b, h, host_cap]     float32, pinned host: importance at the time of eviction;
+ *   pos     [b, h, host_cap]     int32, pinned host: token position;
+ *   len     [b, h]               int32, DEVICE memory: tokens held per (sequence, head) pair.
+ * Rows 0..len-1 of a pair are valid, in the order in which they were evicted.
+ */
+typedef struct {
+    void *k;
+    void *v;
+    float *score;
+    int32_t *pos;
+    int32_t *len;
+    int32_t host_cap;
+} swa_host_store;
+
+/*
+ * Stores what a decode step evicted.  Call between swa_decode_step (two-call form: the cache still
+ * holds every row) and swa_compact_kv: for every pair, the slots of [0, cache_len) that are not in
+ * kept_idx[0 .. kept_cnt) are appended to the pair's host store in ascending slot order (rows of K,
+ * V, score, pos; bit-exact copies) and store->len grows by their number.  Device memory is only read.
+ * A pair whose store has no room is skipped as a whole (nothing written) and the
+ * SWA_ERR_HOST_STORE_FULL status bit is set.  params->len_bound, if set, must bound cache_len.
+ * The copies cross the host link: the call is bound by it, not by HBM.
+ */
+int swa_offload_evicted(const swa_params *params, const void *k_cache, const void *v_cache,
+                        const float *score, const int32_t *pos, const int32_t *kept_idx,
+                        const int32_t *kept_cnt, const int32_t *cache_len,
+                        const swa_host_store *store, void *workspace, void *stream);
+
+/*
+ * Loads tokens back: for every pair, rows req_idx[s, hd, 0 .. req_cnt[s]) of its host store (indices
+ * into the store, 0 <= index < store->len) are appended to the cache at slots cache_len[s] ..., with
+ * their importance and position; new_len[s] = cache_len[s] + req_cnt[s] (cache_len is only read:
+ * pass new_len as cache_len to the next call).  The tokens stay in the store as well.  The cache is
+ * then no longer in token order: continue with the SWA_UNORDERED forms, whose window and tie rules
+ * go by token position.  A sequence without room is skipped (new_len = cache_len, capacity status
+ * bit); an index outside the store sets the SWA_ERR_BAD_REQUEST status bit (row 0 stands in).
+ *   req_idx [b, h, max_req] int32, req_cnt [b] int32 (device), 0 <= req_cnt <= max_req.
+ */
+int swa_reload_tokens(const swa_params *params, const swa_host_store *store, const int32_t *req_idx,
+                      const int32_t *req_cnt, int32_t max_req, void *k_cache, void *v_cache,
+                      float *score, int32_t *pos, const int32_t *cache_len, int32_t *new_len,
+                      void *workspace, void *stream);
 
 /*
  * Measurement aid, not part of the method: reads `bytes` (rounded down to a multiple of 104 KiB)

@@ -20,6 +20,7 @@ SWA_F32, SWA_F16, SWA_BF16 = 0, 1, 2
 SWA_OK = 0
 SWA_ERR_NULL, SWA_ERR_BAD_SHAPE, SWA_ERR_UNSUPPORTED_D, SWA_ERR_UNSUPPORTED_DTYPE = -1, -2, -3, -4
 SWA_ERR_BAD_SPARSITY, SWA_ERR_CAPACITY, SWA_ERR_HIP, SWA_ERR_ALIGNMENT = -5, -6, -7, -8
+SWA_ERR_HOST_STORE_FULL, SWA_ERR_BAD_REQUEST = -9, -10
 SWA_MAX_CAP = 16384
 SWA_MAX_PREFILL_ROWS = 128
 SWA_W_EVEN_SPLIT = -1
@@ -36,7 +37,7 @@ DTYPE_CODE = {torch.float32: SWA_F32, torch.float16: SWA_F16, torch.bfloat16: SW
 EXPORTS = ["swa_strerror", "swa_workspace_bytes", "swa_workspace_init", "swa_check_status",
            "swa_budget", "swa_prefill_scores", "swa_decode_step", "swa_compact_kv", "swa_quantize_kv",
            "swa_decode_step_q8", "swa_prefill_rows", "swa_decode_step_window", "swa_prefill_attention", "swa_probe_stream_read",
-           "swa_prepare", "swa_decode_step_static", "swa_decode_step_window_q8"]
+           "swa_prepare", "swa_decode_step_static", "swa_decode_step_window_q8", "swa_offload_evicted", "swa_reload_tokens"]
 
 
 class SwaParams(ctypes.Structure):
@@ -44,6 +45,11 @@ class SwaParams(ctypes.Structure):
                 ("cap", ctypes.c_int32), ("w", ctypes.c_int32), ("sparsity_bp", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("scale", ctypes.c_float),
                 ("len_bound", ctypes.c_int32), ("flags", ctypes.c_int32)]
+
+
+class SwaHostStore(ctypes.Structure):
+    _fields_ = [("k", ctypes.c_void_p), ("v", ctypes.c_void_p), ("score", ctypes.c_void_p),
+                ("pos", ctypes.c_void_p), ("len", ctypes.c_void_p), ("host_cap", ctypes.c_int32)]
 
 
 class SwaError(RuntimeError):
@@ -96,6 +102,10 @@ def lib():
         L.swa_decode_step_window.argtypes = [pp] + [vp] * 6 + [ctypes.c_int32] * 2 + [vp] * 10
         L.swa_decode_step_window_q8.restype = ctypes.c_int
         L.swa_decode_step_window_q8.argtypes = [pp] + [vp] * 7 + [ctypes.c_int32] * 2 + [vp] * 10
+        L.swa_offload_evicted.restype = ctypes.c_int
+        L.swa_offload_evicted.argtypes = [pp] + [vp] * 7 + [ctypes.POINTER(SwaHostStore), vp, vp]
+        L.swa_reload_tokens.restype = ctypes.c_int
+        L.swa_reload_tokens.argtypes = [pp, ctypes.POINTER(SwaHostStore), vp, vp, ctypes.c_int32] + [vp] * 8
         L.swa_prefill_attention.restype = ctypes.c_int
         L.swa_prefill_attention.argtypes = [pp, vp, vp, vp, i32p, vp, ctypes.c_int32, vp, vp, vp]
         L.swa_probe_stream_read.restype = ctypes.c_int
@@ -236,6 +246,38 @@ def swa_prefill_attention(params: SwaParams, q, k_cache, v_cache, cache_len, out
     _check(lib().swa_prefill_attention(ctypes.byref(params), _ptr(q), _ptr(k_cache), _ptr(v_cache),
                                        _ptr(cache_len), _ptr(out), int(R), _ptr(score),
                                        _ptr(workspace), _stream(stream)), "swa_prefill_attention")
+
+
+class HostStore:
+    """Pinned host tensors of one layer's offload store plus the per-pair counters on the device
+    (allocation plumbing only; the copies run in swa_offload_evicted / swa_reload_tokens)."""
+
+    def __init__(self, params: SwaParams, host_cap: int, device="cuda"):
+        b, h, d = params.b, params.h, params.d
+        dt = torch.uint8 if params.flags & SWA_KV_INT8 else {v: k for k, v in DTYPE_CODE.items()}[params.dtype]
+        self.k = torch.zeros((b, h, host_cap, d), dtype=dt, pin_memory=True)
+        self.v = torch.zeros((b, h, host_cap, d), dtype=dt, pin_memory=True)
+        self.score = torch.zeros((b, h, host_cap), dtype=torch.float32, pin_memory=True)
+        self.pos = torch.full((b, h, host_cap), -1, dtype=torch.int32, pin_memory=True)
+        self.len = torch.zeros((b, h), dtype=torch.int32, device=device)
+        self.host_cap = host_cap
+        self.c = SwaHostStore(self.k.data_ptr(), self.v.data_ptr(), self.score.data_ptr(), self.pos.data_ptr(),
+                              self.len.data_ptr(), host_cap)
+
+
+def swa_offload_evicted(params: SwaParams, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len,
+                        store: HostStore, workspace, stream=None) -> None:
+    _check(lib().swa_offload_evicted(ctypes.byref(params), _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(pos),
+                                     _ptr(kept_idx), _ptr(kept_cnt), _ptr(cache_len), ctypes.byref(store.c),
+                                     _ptr(workspace), _stream(stream)), "swa_offload_evicted")
+
+
+def swa_reload_tokens(params: SwaParams, store: HostStore, req_idx, req_cnt, max_req: int, k_cache, v_cache,
+                      score, pos, cache_len, new_len, workspace, stream=None) -> None:
+    _check(lib().swa_reload_tokens(ctypes.byref(params), ctypes.byref(store.c), _ptr(req_idx), _ptr(req_cnt),
+                                   int(max_req), _ptr(k_cache), _ptr(v_cache), _ptr(score), _ptr(pos),
+                                   _ptr(cache_len), _ptr(new_len), _ptr(workspace), _stream(stream)),
+           "swa_reload_tokens")
 
 
 def swa_probe_stream_read(src, nbytes: int, sink, stream=None) -> None:

@@ -168,6 +168,8 @@ const char* swa_strerror(int code)
         case SWA_ERR_CAPACITY: return "cap exceeds SWA_MAX_CAP, or a sequence's cache was full";
         case SWA_ERR_HIP: return "a HIP runtime call failed";
         case SWA_ERR_ALIGNMENT: return "tensor pointers must be 16-byte aligned";
+        case SWA_ERR_HOST_STORE_FULL: return "a host store had no room for the evicted tokens";
+        case SWA_ERR_BAD_REQUEST: return "a reload named a token that the host store does not hold";
         default: return "unknown swa_status";
     }
 }
@@ -228,7 +230,10 @@ int swa_check_status(const swa_params* params, void* workspace, void* stream, in
                            (int64_t)1);
         if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
     }
-    *status_out = (bits & swa::kStatusCapacityBit) ? SWA_ERR_CAPACITY : SWA_OK;
+    *status_out = (bits & swa::kStatusCapacityBit)     ? SWA_ERR_CAPACITY
+                  : (bits & swa::kStatusHostStoreBit) ? SWA_ERR_HOST_STORE_FULL
+                  : (bits & swa::kStatusBadRequestBit) ? SWA_ERR_BAD_REQUEST
+                                                       : SWA_OK;
     return SWA_OK;
 }
 
@@ -390,6 +395,44 @@ int swa_decode_step_q8(const swa_params* params, const void* q, const void* k_ne
     if (!qparams) return SWA_ERR_NULL;
     return decode_common(params, q, k_new, v_new, k_codes, v_codes, qparams, score, pos, cache_len, seq_len,
                          kept_idx, kept_cnt, out, probs_dbg, workspace, stream);
+}
+
+static int check_store(const swa_host_store* st)
+{
+    if (!st || !st->k || !st->v || !st->score || !st->pos || !st->len) return SWA_ERR_NULL;
+    if (st->host_cap < 1) return SWA_ERR_BAD_SHAPE;
+    if (!swa::aligned16(st->k) || !swa::aligned16(st->v)) return SWA_ERR_ALIGNMENT;
+    return SWA_OK;
+}
+
+int swa_offload_evicted(const swa_params* params, const void* k_cache, const void* v_cache, const float* score,
+                        const int32_t* pos, const int32_t* kept_idx, const int32_t* kept_cnt,
+                        const int32_t* cache_len, const swa_host_store* store, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!k_cache || !v_cache || !score || !pos || !kept_idx || !kept_cnt || !cache_len || !workspace) return SWA_ERR_NULL;
+    rc = check_store(store);
+    if (rc != SWA_OK) return rc;
+    if (!swa::aligned16(k_cache) || !swa::aligned16(v_cache)) return SWA_ERR_ALIGNMENT;
+    return swa::launch_offload(*params, k_cache, v_cache, score, pos, kept_idx, kept_cnt, cache_len, *store, workspace,
+                               static_cast<hipStream_t>(stream));
+}
+
+int swa_reload_tokens(const swa_params* params, const swa_host_store* store, const int32_t* req_idx,
+                      const int32_t* req_cnt, int32_t max_req, void* k_cache, void* v_cache, float* score,
+                      int32_t* pos, const int32_t* cache_len, int32_t* new_len, void* workspace, void* stream)
+{
+    int rc = swa::validate(params);
+    if (rc != SWA_OK) return rc;
+    if (!req_idx || !req_cnt || !k_cache || !v_cache || !score || !pos || !cache_len || !new_len || !workspace)
+        return SWA_ERR_NULL;
+    rc = check_store(store);
+    if (rc != SWA_OK) return rc;
+    if (max_req < 1 || max_req > params->cap || cache_len == new_len) return SWA_ERR_BAD_SHAPE;
+    if (!swa::aligned16(k_cache) || !swa::aligned16(v_cache)) return SWA_ERR_ALIGNMENT;
+    return swa::launch_reload(*params, *store, req_idx, req_cnt, max_req, k_cache, v_cache, score, pos, cache_len,
+                              new_len, workspace, static_cast<hipStream_t>(stream));
 }
 
 int swa_probe_stream_read(const void* src, size_t bytes, void* sink, void* stream)

@@ -15,7 +15,9 @@ constexpr int kWave = 64;
 //   int32 arrive[b]  (at +64 bytes)  per-sequence arrival counters of decode steps
 constexpr size_t kWsStatusOffset = 0;
 constexpr size_t kWsArriveOffset = 64;
-constexpr int32_t kStatusCapacityBit = 1;
+constexpr int32_t kStatusCapacityBit = 1;      // a cache was full (or longer than len_bound)
+constexpr int32_t kStatusHostStoreBit = 2;     // a pair's host store had no room for its evicted tokens
+constexpr int32_t kStatusBadRequestBit = 4;    // a reload asked for a token the host store does not hold
 
 struct F32 {};
 struct F16 {};

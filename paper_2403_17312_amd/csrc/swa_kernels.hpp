@@ -54,6 +54,14 @@ int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* sco
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
                    const int32_t* cache_len, float* score, float* rows, bool q_in_place, hipStream_t stream);
 
+// Token-level offload tier (Section V-A, Algorithm 2): evicted rows to the host store, requested rows back.
+int launch_offload(const swa_params& p, const void* k_cache, const void* v_cache, const float* score,
+                   const int32_t* pos, const int32_t* kept_idx, const int32_t* kept_cnt, const int32_t* cache_len,
+                   const swa_host_store& st, void* workspace, hipStream_t stream);
+int launch_reload(const swa_params& p, const swa_host_store& st, const int32_t* req_idx, const int32_t* req_cnt,
+                  int32_t max_req, void* k_cache, void* v_cache, float* score, int32_t* pos,
+                  const int32_t* cache_len, int32_t* new_len, void* workspace, hipStream_t stream);
+
 // Causal attention over the whole prompt (Eq. 1-2) on MFMA: out[t] for every prompt position.
 int launch_flash_prefill(const swa_params& p, float scale, const void* q, const void* k_cache, const void* v_cache,
                          const int32_t* cache_len, void* out, hipStream_t stream);

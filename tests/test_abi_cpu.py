@@ -50,7 +50,7 @@ def test_params_struct_matches_header(B):
 
 
 def test_strerror_covers_all_codes(B):
-    for code in range(0, -9, -1):
+    for code in range(0, -11, -1):
         msg = B.strerror(code)
         assert msg and "unknown" not in msg
     assert "unknown" in B.strerror(-99)
@@ -225,3 +225,29 @@ def test_binding_fails_loudly_without_the_library(B, monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError, match="missing"):
         B.lib()
+
+
+def test_offload_tier_entry_points_validate_their_arguments(B):
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    p = B.make_params(2, 2, 64, 32, 2, 5000, B.SWA_F16)
+    good = B.SwaHostStore(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 16)
+
+    def off(store=good, k=ok, ws=ok):
+        return L.swa_offload_evicted(ctypes.byref(p), k, ok, ok, ok, ok, ok, ok, ctypes.byref(store) if store else None,
+                                     ws, ok)
+    assert off(store=None) == B.SWA_ERR_NULL
+    assert off(store=B.SwaHostStore(0x1000, 0, 0x1000, 0x1000, 0x1000, 16)) == B.SWA_ERR_NULL
+    assert off(store=B.SwaHostStore(0x1000, 0x1000, 0x1000, 0x1000, 0x1000, 0)) == B.SWA_ERR_BAD_SHAPE
+    assert off(store=B.SwaHostStore(0x1004, 0x1000, 0x1000, 0x1000, 0x1000, 16)) == B.SWA_ERR_ALIGNMENT
+    assert off(k=None) == B.SWA_ERR_NULL
+    assert off(ws=None) == B.SWA_ERR_NULL
+
+    def rel(store=good, max_req=4, cache_len=ctypes.c_void_p(0x2000), new_len=ctypes.c_void_p(0x3000), req=ok):
+        return L.swa_reload_tokens(ctypes.byref(p), ctypes.byref(store) if store else None, req, ok, max_req, ok, ok, ok,
+                                   ok, cache_len, new_len, ok, ok)
+    assert rel(store=None) == B.SWA_ERR_NULL
+    assert rel(req=None) == B.SWA_ERR_NULL
+    assert rel(max_req=0) == B.SWA_ERR_BAD_SHAPE
+    assert rel(max_req=33) == B.SWA_ERR_BAD_SHAPE
+    assert rel(cache_len=ok, new_len=ok) == B.SWA_ERR_BAD_SHAPE        # the new lengths need their own array

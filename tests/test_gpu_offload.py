@@ -1,0 +1,190 @@
+"""GPU tests of the token-level offload tier (swa_offload_evicted, swa_reload_tokens) against the numpy
+oracle in oracle/offload_oracle.py: copies are index and byte work, so everything is compared bit for
+bit; the decode step that follows a reload is compared with the fp64 oracle as usual."""
+import numpy as np
+import pytest
+import torch
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def env():
+    if not torch.cuda.is_available():
+        pytest.fail("GPU tests need a GPU (run with -m 'not gpu' on CPU-only hosts)")
+    from oracle import swa_oracle as O
+    from oracle import offload_oracle as OF
+    from paper_2403_17312_amd import binding as B
+    from paper_2403_17312_amd import workload as W
+    import lockstep as LS
+    O.build()
+    B.lib()
+    return O, OF, B, W, LS
+
+
+def _host(t):
+    """Exact float64 / integer copy of a device or pinned tensor."""
+    return t.detach().to(torch.float64).cpu().numpy().copy() if t.is_floating_point() else t.detach().cpu().numpy().copy()
+
+
+def _same_store(B, store, ref, what):
+    torch.cuda.synchronize()
+    L = store.len.cpu().numpy()
+    assert np.array_equal(L, ref.len), f"{what}: store lengths {L.tolist()} vs {ref.len.tolist()}"
+    gk, gv, gs, gp = _host(store.k), _host(store.v), _host(store.score), store.pos.numpy()
+    for s in range(L.shape[0]):
+        for hd in range(L.shape[1]):
+            n = L[s, hd]
+            assert np.array_equal(gk[s, hd, :n], ref.K[s, hd, :n]), f"{what}: K rows of pair {s},{hd}"
+            assert np.array_equal(gv[s, hd, :n], ref.V[s, hd, :n]), f"{what}: V rows of pair {s},{hd}"
+            assert np.array_equal(gs[s, hd, :n], ref.score[s, hd, :n]), f"{what}: importance of pair {s},{hd}"
+            assert np.array_equal(gp[s, hd, :n], ref.pos[s, hd, :n]), f"{what}: positions of pair {s},{hd}"
+            assert np.all(gp[s, hd, n:] == -1), f"{what}: rows beyond the store's length were written"
+
+
+@pytest.mark.parametrize("dtype,d,q8", [("f16", 128, False), ("bf16", 64, False), ("f32", 128, False), ("f16", 128, True)])
+def test_offload_then_reload_over_a_trajectory(env, dtype, d, q8):
+    O, OF, B, W, LS = env
+    wl = W.Workload(f"t_off_{dtype}_{d}", 71, b=3, h=4, d=d, dtype=dtype, prompt_lo=30, prompt_hi=220, steps=10, w=6,
+                    sparsity_bp=7000, hh_frac=0.02)
+    print(f"  offload tier: {dtype} d={d} int8={q8}", flush=True)
+    _trajectory(env, wl, q8)
+
+
+def test_offload_at_full_size_every_pair(env):
+    # config 2 at full size: the step after the prompt evicts about 410 of 513 tokens of each of the 512 pairs
+    O, OF, B, W, LS = env
+    print("  offload tier: config 2, every pair", flush=True)
+    _trajectory(env, W.CONFIGS["c2_opt6p7b"].replace(steps=4), False)
+
+
+def _trajectory(env, wl, q8):
+    O, OF, B, W, LS = env
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    st = LS.new_state(wl, prompt)
+    st.score.zero_()
+    if q8:
+        st.quantize()
+    store = B.HostStore(st.params, host_cap=wl.cap)
+    ref = OF.HostStore(wl.b, wl.h, wl.d, wl.cap)
+    for t in range(wl.steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        st.decode_step(q, kn, vn)                                  # two-call form: the cache still holds every row
+        snap = [np.nan_to_num(_host(x)) for x in (st.K, st.V, st.score)] + \
+               [_host(x) for x in (st.pos, st.kept_idx, st.kept_cnt, st.cache_len)]
+        B.swa_offload_evicted(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt, st.cache_len, store,
+                              st.workspace)
+        assert OF.offload_evicted(*snap, ref) == []
+        st.compact()
+        _same_store(B, store, ref, f"step {t}")
+    assert st.check_status() == 0
+    assert int(store.len.sum()) > 0
+
+    # ---- load a few stored tokens of every pair back, then step in the unordered fused form ----
+    rng = np.random.default_rng(3)
+    L = store.len.cpu().numpy()
+    max_req = 5
+    req = np.zeros((wl.b, wl.h, max_req), dtype=np.int32)
+    cnt = np.array([min(max_req, int(L[s].min())) for s in range(wl.b)], dtype=np.int32)
+    for s in range(wl.b):
+        for hd in range(wl.h):
+            req[s, hd, :cnt[s]] = rng.choice(L[s, hd], size=cnt[s], replace=False)
+    Kc, Vc, sc, pc, lc = (np.nan_to_num(_host(st.K)), np.nan_to_num(_host(st.V)), np.nan_to_num(_host(st.score)),
+                          _host(st.pos), _host(st.cache_len))
+    new_len = torch.zeros_like(st.cache_len)
+    B.swa_reload_tokens(st.params, store, torch.tensor(req, device="cuda"), torch.tensor(cnt, device="cuda"), max_req,
+                        st.K, st.V, st.score, st.pos, st.cache_len, new_len, st.workspace)
+    want_len = OF.reload_tokens(ref, req, cnt, Kc, Vc, sc, pc, lc)
+    assert np.array_equal(new_len.cpu().numpy(), want_len) and np.all(want_len == lc + cnt)
+    gK, gV, gs, gp = np.nan_to_num(_host(st.K)), np.nan_to_num(_host(st.V)), np.nan_to_num(_host(st.score)), _host(st.pos)
+    for s in range(wl.b):
+        n = want_len[s]
+        assert np.array_equal(gK[s, :, :n], Kc[s, :, :n]) and np.array_equal(gV[s, :, :n], Vc[s, :, :n])
+        assert np.array_equal(gs[s, :, :n], sc[s, :, :n]) and np.array_equal(gp[s, :, :n], pc[s, :, :n])
+    assert st.check_status() == 0
+    if q8:
+        return                                                     # the step after a reload is checked on the plain caches
+    # one decode step over the merged cache, unordered fused form, against the oracle on the cache
+    # brought into token order
+    st.cache_len.copy_(new_len)
+    st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+    q, kn, vn = W.make_step(wl, wl.steps, prompt["mu"])
+    st.seq_len += 1
+    n_o = st.seq_len.cpu().numpy()
+    st.decode_compact_step(q, kn, vn)
+    probs = _host(st.probs)
+    out_g = _host(st.out)
+    q_o, kn_o, vn_o = _host(q), _host(kn), _host(vn)
+    for s in range(wl.b):
+        m0 = int(want_len[s])
+        for hd in range(wl.h):
+            order = np.argsort(pc[s, hd, :m0], kind="stable")
+            Ks = np.zeros((1, 1, m0 + 1, wl.d))
+            Vs = np.zeros((1, 1, m0 + 1, wl.d))
+            Ks[0, 0, :m0], Vs[0, 0, :m0] = Kc[s, hd, order], Vc[s, hd, order]
+            ss = np.zeros((1, 1, m0 + 1))
+            ss[0, 0, :m0] = sc[s, hd, order]
+            ps = np.full((1, 1, m0 + 1), -1, dtype=np.int32)
+            ps[0, 0, :m0] = pc[s, hd, order]
+            cl = np.array([m0], dtype=np.int32)
+            kept, kc, out_o, p_o = O.decode_step(q_o[s:s + 1, hd:hd + 1], kn_o[s:s + 1, hd:hd + 1], vn_o[s:s + 1, hd:hd + 1],
+                                                 Ks, Vs, ss, ps, cl, n_o[s:s + 1], wl.w, wl.sparsity_bp, wl.scale)
+            p_g = np.concatenate([probs[s, hd, :m0][order], probs[s, hd, m0:m0 + 1]])
+            assert np.all(np.abs(p_g - p_o[0, 0, :m0 + 1]) <= 1e-5 * p_o[0, 0, :m0 + 1] + 1e-12)
+            # the tokens the GPU kept, by position, against the oracle's choice (importance values here are far
+            # apart: the reloaded tokens carry their old sums, the others have grown since)
+            c = int(st.cache_len[s])
+            got = sorted(_host(st.pos)[s, hd, :c].tolist())
+            want = sorted(ps[0, 0, kept[0, 0, :kc[0]]].tolist())
+            assert c == kc[0]
+            if got == want:
+                LS.check_out(out_g[s:s + 1, hd:hd + 1], out_o, wl.dtype, f"step after reload, pair {s},{hd}")
+            else:                                                  # only a near tie may flip a token
+                diff = set(got) ^ set(want)
+                nl = O.budget(int(n_o[s]), m0 + 1, wl.w, wl.sparsity_bp)[1]
+                cut = np.sort(ss[0, 0, :m0 + 1 - nl])[::-1][kc[0] - nl - 1]
+                for tp in diff:
+                    j = int(np.where(ps[0, 0] == tp)[0][0])
+                    assert abs(ss[0, 0, j] - cut) <= 2e-5 * abs(cut), "a kept set that differs by more than a near tie"
+
+
+def test_offload_reports_a_full_store_and_reload_a_bad_request(env):
+    O, OF, B, W, LS = env
+    wl = W.Workload("t_off_full", 72, b=2, h=2, d=128, dtype="f16", prompt_lo=60, prompt_hi=90, steps=2, w=4,
+                    sparsity_bp=8000, hh_frac=0.02)
+    prompt = W.make_prompt(wl, "cuda")
+    st = LS.new_state(wl, prompt)
+    st.score.zero_()
+    store = B.HostStore(st.params, host_cap=8)                     # the first step evicts far more than 8 tokens
+    q, kn, vn = W.make_step(wl, 0, prompt["mu"])
+    st.seq_len += 1
+    st.decode_step(q, kn, vn)
+    B.swa_offload_evicted(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt, st.cache_len, store,
+                          st.workspace)
+    assert st.check_status() == B.SWA_ERR_HOST_STORE_FULL
+    assert int(store.len.sum()) == 0 and bool((store.pos == -1).all())
+    st.compact()
+    # a second, steady step evicts one token per pair: that fits
+    q, kn, vn = W.make_step(wl, 1, prompt["mu"])
+    st.seq_len += 1
+    st.decode_step(q, kn, vn)
+    B.swa_offload_evicted(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt, st.cache_len, store,
+                          st.workspace)
+    st.compact()
+    assert st.check_status() == 0
+    L = store.len.cpu().numpy()
+    assert np.all(L >= 0) and L.sum() > 0
+    # a request for a row the store does not hold is reported; a request that does not fit is skipped
+    req = torch.full((wl.b, wl.h, 2), 7, dtype=torch.int32, device="cuda")
+    cnt = torch.tensor([1, 1], dtype=torch.int32, device="cuda")
+    new_len = torch.zeros_like(st.cache_len)
+    B.swa_reload_tokens(st.params, store, req, cnt, 2, st.K, st.V, st.score, st.pos, st.cache_len, new_len, st.workspace)
+    assert st.check_status() == B.SWA_ERR_BAD_REQUEST
+    K0 = st.K.clone()
+    full = torch.full_like(st.cache_len, wl.cap - 1)
+    cnt2 = torch.tensor([2, 2], dtype=torch.int32, device="cuda")
+    B.swa_reload_tokens(st.params, store, torch.zeros_like(req), cnt2, 2, st.K, st.V, st.score, st.pos, full, new_len,
+                        st.workspace)
+    assert st.check_status() == B.SWA_ERR_CAPACITY
+    assert new_len.tolist() == [wl.cap - 1] * 2 and torch.equal(st.K.view(torch.int16), K0.view(torch.int16))
