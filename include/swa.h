@@ -146,6 +146,20 @@ typedef struct {
  */
 int swa_prepare(void);
 
+/*
+ * swa_params.flags bit, on its own (the two-call form: swa_decode_step, then swa_compact_kv whenever
+ * the caller wants): the rows of one (sequence, head) pair are split over several workgroups.  For
+ * few pairs with long caches - small batches, long contexts, caches that are compacted rarely or
+ * never - one workgroup per pair leaves most of the GPU idle.  The call then enqueues four kernels
+ * (logits of a slice of the keys per workgroup; softmax, importance and selection per pair;
+ * partial outputs over slices of the kept list; their sum) and needs the larger workspace that
+ * swa_workspace_bytes reports for this flag.  Attention weights, importance and the kept set are
+ * bit-identical to the one-workgroup form; the output's partial sums are added in another order.
+ * With many pairs or short caches (fewer than 256 rows per pair, or 1024 pairs and more) the call
+ * falls back to the one-workgroup kernel.
+ */
+#define SWA_SPLIT_ROWS 16
+
 /* Message for a swa_status code (static storage, never NULL). */
 const char *swa_strerror(int code);
 

@@ -30,6 +30,7 @@ SWA_UNORDERED = 2
 SWA_HEAD_SHARED = 4
 SWA_MAX_UNORDERED_SLOTS = 7168
 SWA_KV_INT8 = 8
+SWA_SPLIT_ROWS = 16
 SWA_MAX_WINDOW_ROWS = 64
 SWA_STATIC_SCRATCH_BYTES = 8 << 20
 

@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB_PATH = os.path.join(HERE, "libswa_hip.so")
-SOURCES = ["swa_api.hip", "swa_decode.hip", "swa_compact.hip", "swa_prefill.hip", "swa_quant.hip", "swa_flash.hip", "swa_offload.hip"]
+SOURCES = ["swa_api.hip", "swa_decode.hip", "swa_compact.hip", "swa_prefill.hip", "swa_quant.hip", "swa_flash.hip", "swa_offload.hip", "swa_splitk.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",

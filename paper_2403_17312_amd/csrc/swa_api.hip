@@ -35,6 +35,16 @@ size_t shared_workspace_offset(const swa_params& p)
     return (head + 255) & ~(size_t)255;
 }
 
+int split_factor(int64_t pairs, int len_bound)
+{
+    // enough workgroups to put about four on every CU, every slice at least 128 rows long
+    int64_t g = (1024 + pairs - 1) / pairs;
+    const int by_rows = len_bound / 128;
+    if (g > by_rows) g = by_rows;
+    if (g > kMaxSplit) g = kMaxSplit;
+    return g < 1 ? 1 : (int)g;
+}
+
 int decode_stash_rows(const swa_params& p)
 {
     // window + a margin for evictions a little behind it; bounded so LDS keeps several
@@ -137,7 +147,8 @@ static int validate(const swa_params* p)
     if (p->sparsity_bp < 0 || p->sparsity_bp > 9999) return SWA_ERR_BAD_SPARSITY;
     if (!(p->scale >= 0.f) || isinf(p->scale)) return SWA_ERR_BAD_SHAPE;
     if (p->len_bound < 0) return SWA_ERR_BAD_SHAPE;
-    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED | SWA_HEAD_SHARED | SWA_KV_INT8)) return SWA_ERR_BAD_SHAPE;
+    if (p->flags & ~(SWA_FUSE_COMPACTION | SWA_UNORDERED | SWA_HEAD_SHARED | SWA_KV_INT8 | SWA_SPLIT_ROWS)) return SWA_ERR_BAD_SHAPE;
+    if ((p->flags & SWA_SPLIT_ROWS) && p->flags != SWA_SPLIT_ROWS) return SWA_ERR_BAD_SHAPE;   // two-call form only
     if ((p->flags & SWA_KV_INT8) && p->dtype != SWA_F16) return SWA_ERR_UNSUPPORTED_DTYPE;
     if ((p->flags & SWA_UNORDERED) && !(p->flags & SWA_FUSE_COMPACTION)) return SWA_ERR_BAD_SHAPE;
     if ((p->flags & SWA_HEAD_SHARED) && !(p->flags & SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
@@ -181,6 +192,10 @@ size_t swa_workspace_bytes(const swa_params* params)
     if (params->flags & SWA_HEAD_SHARED)
         bytes += sizeof(float) * ((size_t)params->b * params->h * params->cap * 2 + (size_t)params->b * params->h * params->d +
                                   (size_t)params->b * params->cap);
+    if (params->flags & SWA_SPLIT_ROWS)
+        bytes += sizeof(float) * ((size_t)params->b * params->h * params->cap * 2 +
+                                  (size_t)params->b * params->h * swa::kMaxSplit * (params->d + 1) +
+                                  (size_t)params->b * params->h);
     return (bytes + 255) & ~(size_t)255;
 }
 
@@ -312,7 +327,7 @@ static int window_common(const swa_params* params, const void* q, const void* k_
                          void* stream)
 {
     // the ring's columns follow their tokens through the hole-filling compaction only
-    const int32_t form = params->flags & ~(SWA_HEAD_SHARED | SWA_KV_INT8);
+    const int32_t form = params->flags & ~(SWA_HEAD_SHARED | SWA_KV_INT8);   // (SWA_SPLIT_ROWS is refused here)
     if (form != (SWA_FUSE_COMPACTION | SWA_UNORDERED)) return SWA_ERR_BAD_SHAPE;
     if (!ring) return SWA_ERR_NULL;
     if (R < 1 || R > SWA_MAX_WINDOW_ROWS || ring_row < 0 || ring_row >= R) return SWA_ERR_BAD_SHAPE;

@@ -67,7 +67,11 @@ struct DecodeArgs {
     // new importance, the attention weights and the dense output of every pair; a small kernel
     // sums the new importance over the heads of every sequence; phase 2 selects from that sum
     // (every head of a sequence reaches the same decision) and finishes output and compaction.
-    int32_t phase;        // 0 = whole step in one launch
+    int32_t phase;        // 0 = whole step in one launch; 1, 2 = the two halves of the head-shared
+                          // step; 3 = rows split over workgroups: the logits come from ws_z, and the
+                          // weights go to ws_p for the launches that form the output
+    const float* ws_z;    // [b,h,cap] logits of the split step
+    int32_t* ws_ok;       // [b,h]     split step: set to 1 when the pair's step has run (not skipped)
     float* ws_p;          // [b,h,cap] attention weights of phase 1
     float* ws_snew;       // [b,h,cap] new importance of phase 1
     float* ws_abar;       // [b,h,d]   dense attention output of phase 1
@@ -189,7 +193,7 @@ swa_decode_kernel(DecodeArgs a)
     // (Not for the 8-bit cache: its lanes have no registers to spare, and it measured slower.)
     constexpr bool kEarlyStage = !kQ8;
     Vec16 k0[UF], v0[UF];
-    if (kEarlyStage && a.phase != 2) {
+    if (kEarlyStage && a.phase != 2 && a.phase != 3) {
         const char* Kq = a.k_cache + pair * (int64_t)a.cap * ROWB;
         const char* Vq = a.v_cache + pair * (int64_t)a.cap * ROWB;
 #pragma unroll
@@ -268,7 +272,7 @@ swa_decode_kernel(DecodeArgs a)
         const int ncand = m - n_local;
         const int wlo = n - w_eff;                    // unordered layout: the window is pos >= wlo
         const int E = m - keep;                       // evictions of this step
-        const bool fused = (E <= kMaxFix) && (8 * E <= m);
+        const bool fused = (E <= kMaxFix) && (8 * E <= m) && a.phase != 3;
         // first stashed slot (m = nothing stashed: only the streaming schedule fills the stash)
         const int stash_lo = (fc && fused) ? (m > a.stash_rows ? m - a.stash_rows : 0) : m;
 
@@ -406,6 +410,16 @@ swa_decode_kernel(DecodeArgs a)
                 s_redA[wave] = Mg;
                 s_wS[wave] = Sg;
             }
+        } else if (a.phase == 3) {
+            // ---- rows split over workgroups: the logits were formed by the launch before ----
+            const float* Zp = a.ws_z + pair * (int64_t)cap;
+            for (int i = tid; i < m; i += NT) {
+                const float d = Zp[i];
+                s_p[i] = d;
+                Mg = fmaxf(Mg, d);
+            }
+            Mg = wave_max(Mg);
+            if (lane == 0) s_redA[wave] = Mg;
         } else {
             // ---- key-only pass -------------------------------------------------------
             if (fc) new_row_ready();
@@ -512,10 +526,8 @@ swa_decode_kernel(DecodeArgs a)
                 } else {
                     Sp[i] = sc;
                 }
-                if (a.phase == 1) {
-                    a.ws_snew[pair * (int64_t)cap + i] = sc;
-                    a.ws_p[pair * (int64_t)cap + i] = p;
-                }
+                if (a.phase == 1) a.ws_snew[pair * (int64_t)cap + i] = sc;
+                if (a.phase == 1 || a.phase == 3) a.ws_p[pair * (int64_t)cap + i] = p;
                 const uint32_t key = order_key(sc);
                 s_key[i] = key;
                 if (bag ? (pold[k] < wlo) : (i < ncand)) {
@@ -539,10 +551,8 @@ swa_decode_kernel(DecodeArgs a)
             } else {
                 Sp[i] = sc;
             }
-            if (a.phase == 1) {
-                a.ws_snew[pair * (int64_t)cap + i] = sc;
-                a.ws_p[pair * (int64_t)cap + i] = p;
-            }
+            if (a.phase == 1) a.ws_snew[pair * (int64_t)cap + i] = sc;
+            if (a.phase == 1 || a.phase == 3) a.ws_p[pair * (int64_t)cap + i] = p;
             const uint32_t key = order_key(sc);
             s_key[i] = key;
             if (bag ? (posi < wlo) : (i < ncand)) {
@@ -689,69 +699,99 @@ swa_decode_kernel(DecodeArgs a)
                     rem = s_sel[1];
                 }
             }
+            // Both compactions below give every thread a contiguous run of `per` slots (at most 64:
+            // a cache has at most 16384 slots and long caches get 256 threads or more), so a
+            // thread's decisions fit one 64-bit mask and their order needs two block-wide prefix
+            // sums instead of a ballot and two barriers per 64 slots.
+            const int per = (m + NT - 1) / NT;
+            const int lo = tid * per;
+            const int hi = lo + per < m ? lo + per : m;
+            // exclusive prefix sum over the threads of the workgroup, and the total
+            auto block_scan = [&](int v, int& before, int& total) {
+                int inc = v;
+#pragma unroll
+                for (int o = 1; o < kWave; o <<= 1) {
+                    const int t = __shfl_up(inc, o, kWave);
+                    if (lane >= o) inc += t;
+                }
+                if (lane == kWave - 1) s_wcnt[0][wave] = inc;
+                __syncthreads();
+                int wb = 0, tot = 0;
+#pragma unroll
+                for (int v2 = 0; v2 < NW; ++v2) {
+                    const int c = s_wcnt[0][v2];
+                    if (v2 < wave) wb += c;
+                    tot += c;
+                }
+                before = wb + inc - v;
+                total = tot;
+                __syncthreads();
+            };
             if (bag) {
                 // ---- unordered layout: holes below `keep` are filled by kept rows above it ----
                 // A candidate is kept if its key exceeds the threshold, or equals it and is one of
                 // the `rem` earliest tokens among the equals (rank by position, found by a scan
                 // of the candidates only when some equal key has to lose).
                 const int n_eq = (n_global > 0) ? s_sel[2] : 0;
-                int run_h = 0, run_m = 0;
-                const uint64_t lt = (1ull << lane) - 1ull;
-                for (int base = 0; base < m; base += NT) {
-                    const int i = base + tid;
+                uint64_t keptm = 0ull;
+                for (int k = 0; k < per; ++k) {
+                    const int i = lo + k;
+                    if (i >= hi) break;
                     bool kept = false;
-                    if (i < m) {
-                        const int posi = s_pos[i];
-                        if (posi >= wlo) {
+                    const int posi = s_pos[i];
+                    if (posi >= wlo) {
+                        kept = true;
+                    } else if (n_global > 0) {
+                        const uint32_t key = s_key[i];
+                        if (key > prefix) {
                             kept = true;
-                        } else if (n_global > 0) {
-                            const uint32_t key = s_key[i];
-                            if (key > prefix) {
+                        } else if (key == prefix) {
+                            if (n_eq == rem) {
                                 kept = true;
-                            } else if (key == prefix) {
-                                if (n_eq == rem) {
-                                    kept = true;
-                                } else {
-                                    int rank = 0;
-                                    for (int j = 0; j < m; ++j)
-                                        rank += (s_key[j] == prefix && s_pos[j] < posi) ? 1 : 0;
-                                    kept = rank < rem;
-                                }
+                            } else {
+                                int rank = 0;
+                                for (int j = 0; j < m; ++j)
+                                    rank += (s_key[j] == prefix && s_pos[j] < posi) ? 1 : 0;
+                                kept = rank < rem;
                             }
                         }
                     }
-                    const bool hole = (i < keep) && !kept;
-                    const bool mover = (i >= keep) && (i < m) && kept;
-                    const uint64_t hm = __ballot(hole);
-                    const uint64_t mm = __ballot(mover);
-                    if (lane == 0) {
-                        s_wcnt[0][wave] = __popcll(hm);
-                        s_wcnt[1][wave] = __popcll(mm);
-                    }
-                    __syncthreads();
-                    int hr = run_h + __popcll(hm & lt), mr = run_m + __popcll(mm & lt);
-                    int h_all = 0, m_all = 0;
-#pragma unroll
-                    for (int v = 0; v < NW; ++v) {
-                        const int ch = s_wcnt[0][v], cm = s_wcnt[1][v];
-                        if (v < wave) {
-                            hr += ch;
-                            mr += cm;
+                    if (kept) keptm |= 1ull << k;
+                }
+                // holes (low half) and movers (high half) of this thread's run, counted together
+                int nh = 0, nm = 0;
+                for (int k = 0; k < per; ++k) {
+                    const int i = lo + k;
+                    if (i >= hi) break;
+                    const bool kept = (keptm >> k) & 1ull;
+                    nh += (i < keep && !kept) ? 1 : 0;
+                    nm += (i >= keep && kept) ? 1 : 0;
+                }
+                int before = 0, total = 0;
+                block_scan(nh | (nm << 16), before, total);
+                int hr = before & 0xffff, mr = before >> 16;
+                const int run_h = total & 0xffff, run_m = total >> 16;
+                for (int k = 0; k < per; ++k) {
+                    const int i = lo + k;
+                    if (i >= hi) break;
+                    const bool kept = (keptm >> k) & 1ull;
+                    if (i < keep) {
+                        if (kept) {
+                            s_src[i] = (uint16_t)i;
+                        } else {
+                            if (hr < a.lds_slots / 2) s_holes[hr] = (uint16_t)i;
+                            ++hr;
                         }
-                        h_all += ch;
-                        m_all += cm;
+                    } else if (kept) {
+                        if (mr < a.lds_slots / 2) s_movers[mr] = (uint16_t)i;
+                        ++mr;
                     }
-                    if (i < keep && kept) s_src[i] = (uint16_t)i;
-                    if (hole && hr < a.lds_slots / 2) s_holes[hr] = (uint16_t)i;
-                    if (mover && mr < a.lds_slots / 2) s_movers[mr] = (uint16_t)i;
-                    if (fused && i < m && !kept) {
+                    if (fused && !kept) {
                         const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
                         if (e < kMaxFix) s_evict[e] = i;
                     }
-                    run_h += h_all;
-                    run_m += m_all;
-                    __syncthreads();
                 }
+                __syncthreads();
                 n_moves = run_h < run_m ? run_h : run_m;
                 n_moves = n_moves < a.lds_slots / 2 ? n_moves : a.lds_slots / 2;
                 for (int k = tid; k < run_h; k += NT) {
@@ -762,47 +802,48 @@ swa_decode_kernel(DecodeArgs a)
                     for (int j = tid; j < keep; j += NT) kout[j] = s_src[j];
             } else {
             // Ordered compaction of the kept flags.  A candidate is kept if its key
-            // exceeds the threshold, or equals it and is among the first `rem` equals.
-            int run_out = 0, run_eq = 0;
-            const uint64_t lt = (1ull << lane) - 1ull;
-            for (int base = 0; base < m; base += NT) {
-                const int i = base + tid;
-                const bool is_cand = i < ncand;
-                const uint32_t key = is_cand ? s_key[i] : 0u;
-                const bool is_eq = is_cand && n_global > 0 && key == prefix;
-                const uint64_t eqm = __ballot(is_eq);
-                if (lane == 0) s_wcnt[0][wave] = __popcll(eqm);
-                __syncthreads();
-                int eq_rank = run_eq + __popcll(eqm & lt);
-                int eq_all = 0;
-#pragma unroll
-                for (int v = 0; v < NW; ++v) {
-                    const int c = s_wcnt[0][v];
-                    if (v < wave) eq_rank += c;
-                    eq_all += c;
+            // exceeds the threshold, or equals it and is among the first `rem` equals.  Every key
+            // is read before the first barrier of the prefix sums, the list (which lies over the
+            // key array) is written after them.
+            uint64_t surem = 0ull, eqm = 0ull;      // kept for sure / equal to the threshold
+            for (int k = 0; k < per; ++k) {
+                const int i = lo + k;
+                if (i >= hi) break;
+                if (i >= ncand) {
+                    surem |= 1ull << k;
+                } else if (n_global > 0) {
+                    const uint32_t key = s_key[i];
+                    if (key > prefix) surem |= 1ull << k;
+                    else if (key == prefix) eqm |= 1ull << k;
                 }
-                const bool kept = (i < m) && (!is_cand || (n_global > 0 && key > prefix) ||
-                                              (is_eq && eq_rank < rem));
-                const uint64_t km = __ballot(kept);
-                if (lane == 0) s_wcnt[1][wave] = __popcll(km);
-                __syncthreads();
-                int out_pos = run_out + __popcll(km & lt);
-                int k_all = 0;
-#pragma unroll
-                for (int v = 0; v < NW; ++v) {
-                    const int c = s_wcnt[1][v];
-                    if (v < wave) out_pos += c;
-                    k_all += c;
+            }
+            int eq_before = 0, eq_total = 0;
+            block_scan((int)__popcll(eqm), eq_before, eq_total);
+            // the first (rem - eq_before) equals of this run are kept
+            uint64_t keptm = surem;
+            {
+                int take = rem - eq_before;
+                uint64_t e = eqm;
+                while (take > 0 && e != 0ull) {
+                    const uint64_t low = e & (~e + 1ull);
+                    keptm |= low;
+                    e ^= low;
+                    --take;
                 }
-                if (kept) s_kept[out_pos] = (uint16_t)i;
-                if (fused && i < m && !kept) {
+            }
+            int out_pos = 0, out_total = 0;
+            block_scan((int)__popcll(keptm), out_pos, out_total);
+            for (int k = 0; k < per; ++k) {
+                const int i = lo + k;
+                if (i >= hi) break;
+                if ((keptm >> k) & 1ull) {
+                    s_kept[out_pos++] = (uint16_t)i;
+                } else if (fused) {
                     const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
                     if (e < kMaxFix) s_evict[e] = i;
                 }
-                run_eq += eq_all;
-                run_out += k_all;
-                __syncthreads();
             }
+            __syncthreads();
             if (kout)
                 for (int j = tid; j < keep; j += NT) kout[j] = s_kept[j];
             }
@@ -858,7 +899,7 @@ swa_decode_kernel(DecodeArgs a)
                 for (int k = 0; k < ec; ++k) t -= s_fix[k * D + e];
                 write_out(e, t / (1.f - pe));
             }
-        } else {
+        } else if (a.phase != 3) {       // (phase 3: the output is formed by the launches that follow)
             // gathered pass over the kept value rows: sum_kept p_i v_i / sum_kept p_i.
             // Unordered layout with many evictions (the step after a prompt): the rows that change
             // slot are moved inside this pass, so that the whole step needs one more memory round
@@ -1096,6 +1137,7 @@ swa_decode_kernel(DecodeArgs a)
             atomicOr(a.status, kStatusCapacityBit);
         } else {
             a.kept_cnt[s] = keep;
+            if (a.phase == 3) a.ws_ok[pair] = 1;
         }
         const int old = atomicAdd(&a.arrive[s], 1);
         if (old == a.h - 1) {
@@ -1243,6 +1285,8 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
     a.unordered = (a.fuse_compaction && (p.flags & SWA_UNORDERED)) ? 1 : 0;
     const bool shared = a.unordered && (p.flags & SWA_HEAD_SHARED);
     a.phase = 0;
+    a.ws_z = nullptr;
+    a.ws_ok = nullptr;
     a.ws_p = a.ws_snew = a.ws_abar = a.ws_tot = nullptr;
     if (shared) {
         char* base = static_cast<char*>(workspace) + shared_workspace_offset(p);
@@ -1274,6 +1318,30 @@ int launch_decode(const swa_params& p, float scale, const void* q, const void* k
         return p.d == 64 ? launch_decode_t<BF16, 64>(args, pairs, lds_bytes, nt, stream)
                          : launch_decode_t<BF16, 128>(args, pairs, lds_bytes, nt, stream);
     };
+    if (p.flags & SWA_SPLIT_ROWS) {
+        // rows of a pair over G workgroups: logits, then selection (this kernel, phase 3), then the output
+        const int G = split_factor(pairs, bound);
+        if (G > 1) {
+            char* base = static_cast<char*>(workspace) + shared_workspace_offset(p);
+            const size_t slab = (size_t)p.b * p.h * p.cap * sizeof(float);
+            float* ws_z = reinterpret_cast<float*>(base);
+            float* ws_pp = reinterpret_cast<float*>(base + slab);
+            float* ws_part = reinterpret_cast<float*>(base + 2 * slab);
+            int32_t* ws_ok = reinterpret_cast<int32_t*>(base + 2 * slab +
+                                                        (size_t)pairs * kMaxSplit * (p.d + 1) * sizeof(float));
+            int rc = launch_split(p, scale, 1, G, q, k_new, v_new, k_cache, v_cache, cache_len, kept_idx, kept_cnt,
+                                  ws_z, ws_pp, ws_part, ws_ok, out, stream);
+            if (rc != SWA_OK) return rc;
+            a.phase = 3;
+            a.ws_z = ws_z;
+            a.ws_p = ws_pp;
+            a.ws_ok = ws_ok;
+            rc = launch(a);
+            if (rc != SWA_OK) return rc;
+            return launch_split(p, scale, 2, G, q, k_new, v_new, k_cache, v_cache, cache_len, kept_idx, kept_cnt,
+                                ws_z, ws_pp, ws_part, ws_ok, out, stream);
+        }
+    }
     if (!shared) return launch(a);
     a.phase = 1;
     int rc = launch(a);

@@ -54,6 +54,16 @@ int launch_compact(const swa_params& p, void* k_cache, void* v_cache, float* sco
 int launch_prefill(const swa_params& p, float scale, const void* q_tail, int32_t R, const void* k_cache,
                    const int32_t* cache_len, float* score, float* rows, bool q_in_place, hipStream_t stream);
 
+// SWA_SPLIT_ROWS: workgroups per pair for this many pairs and this bound on the cached length
+// (1 = the one-workgroup kernel serves the call), and the launches around the selection launch
+// (which = 1: logits of every cached key to ws_z; which = 2: output from ws_p and the kept list).
+constexpr int kMaxSplit = 16;
+int split_factor(int64_t pairs, int len_bound);
+int launch_split(const swa_params& p, float scale, int which, int G, const void* q, const void* k_new,
+                 const void* v_new, const void* k_cache, const void* v_cache, const int32_t* cache_len,
+                 const int32_t* kept_idx, const int32_t* kept_cnt, float* ws_z, float* ws_p, float* ws_part,
+                 int32_t* ws_ok, void* out, hipStream_t stream);
+
 // Token-level offload tier (Section V-A, Algorithm 2): evicted rows to the host store, requested rows back.
 int launch_offload(const swa_params& p, const void* k_cache, const void* v_cache, const float* score,
                    const int32_t* pos, const int32_t* kept_idx, const int32_t* kept_cnt, const int32_t* cache_len,

@@ -95,7 +95,7 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
                  prompt: Optional[dict] = None, verbose: bool = False,
                  use_len_bound: bool = False, fused: bool = False, unordered: bool = False,
                  sparsity_of_step=None, head_shared: bool = False, kv_int8: bool = False,
-                 twin: bool = False, twin_kv_every: int = 1) -> Report:
+                 twin: bool = False, twin_kv_every: int = 1, split_rows: bool = False) -> Report:
     """Runs the whole trajectory on the GPU; checks the sampled pairs every step.
 
     twin: a second full-size state is stepped beside the checked one in the call form that
@@ -122,13 +122,18 @@ def run_lockstep(wl: W.Workload, device="cuda", steps: Optional[int] = None,
             B.swa_workspace_init(st.params, st.workspace)
     else:
         assert not unordered
+        if split_rows:
+            # two-call form with one pair's rows split over several workgroups
+            st.params.flags = B.SWA_SPLIT_ROWS
+            st.workspace = torch.zeros((B.swa_workspace_bytes(st.params),), dtype=torch.uint8, device=device)
+            B.swa_workspace_init(st.params, st.workspace)
     tw = None
     if twin:
         tw = new_state(wl, dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone()),
                        debug_probs=False)
         tw.params.flags = st.params.flags
         tw.kept_idx.fill_(-7)                                  # must stay untouched in the fused forms
-        if head_shared:
+        if head_shared or split_rows:
             tw.workspace = torch.zeros((B.swa_workspace_bytes(tw.params),), dtype=torch.uint8, device=device)
             B.swa_workspace_init(tw.params, tw.workspace)
     # Unordered compaction keeps the cache as a set: every GPU tensor is brought into token order

@@ -47,6 +47,8 @@ def test_params_struct_matches_header(B):
     assert int(re.search(r"#define SWA_UNORDERED (\d+)", text).group(1)) == B.SWA_UNORDERED
     assert int(re.search(r"#define SWA_HEAD_SHARED (\d+)", text).group(1)) == B.SWA_HEAD_SHARED
     assert int(re.search(r"#define SWA_MAX_UNORDERED_SLOTS (\d+)", text).group(1)) == B.SWA_MAX_UNORDERED_SLOTS
+    assert int(re.search(r"#define SWA_SPLIT_ROWS (\d+)", text).group(1)) == B.SWA_SPLIT_ROWS
+    assert int(re.search(r"#define SWA_KV_INT8 (\d+)", text).group(1)) == B.SWA_KV_INT8
 
 
 def test_strerror_covers_all_codes(B):
@@ -91,7 +93,8 @@ def test_workspace_bytes(B):
     (dict(flags=2), "SWA_ERR_BAD_SHAPE"),          # SWA_UNORDERED needs SWA_FUSE_COMPACTION
     (dict(flags=4), "SWA_ERR_BAD_SHAPE"),          # SWA_HEAD_SHARED needs the other two
     (dict(flags=5), "SWA_ERR_BAD_SHAPE"),
-    (dict(flags=16), "SWA_ERR_BAD_SHAPE"),
+    (dict(flags=32), "SWA_ERR_BAD_SHAPE"),         # not a flag
+    (dict(flags=17), "SWA_ERR_BAD_SHAPE"),         # SWA_SPLIT_ROWS goes with the two-call form only
     (dict(flags=8), "SWA_ERR_UNSUPPORTED_DTYPE"),  # SWA_KV_INT8 goes with fp16 rows only
     (dict(sparsity_bp=10000), "SWA_ERR_BAD_SPARSITY"),
     (dict(sparsity_bp=-1), "SWA_ERR_BAD_SPARSITY"),

@@ -290,6 +290,63 @@ def test_strict_window_on_the_compressed_cache_and_with_the_head_reduced_set(env
     assert rep.steps == 32
 
 
+def test_rows_split_over_workgroups_matches_the_oracle_and_the_one_workgroup_form(env):
+    # SWA_SPLIT_ROWS: few pairs with long caches; the step runs as four launches
+    O, B, W, LS = env
+    for dtype, d, b, h, hi, ce in [("f16", 128, 1, 4, 2500, 0), ("bf16", 128, 2, 2, 1800, 3), ("f32", 64, 1, 3, 1500, 1),
+                                   ("f16", 64, 2, 3, 900, 0), ("bf16", 64, 1, 1, 5000, 2)]:
+        wl = W.Workload(f"t_split_{dtype}_{d}", 81, b=b, h=h, d=d, dtype=dtype, prompt_lo=hi // 2, prompt_hi=hi, steps=6,
+                        w=16, sparsity_bp=8000, hh_frac=0.01, prefill_R=8)
+        _say(f"  split rows: {dtype} d={d} b={b} h={h} prompts {hi // 2}..{hi}, compaction every {ce}")
+        assert B.swa_workspace_bytes(B.make_params(b, h, d, wl.cap, 16, 8000, wl.torch_dtype, flags=B.SWA_SPLIT_ROWS)) > \
+            2 * 4 * b * h * wl.cap
+        rep = LS.run_lockstep(wl, compact_every=ce, split_rows=True, use_len_bound=True, twin=True)
+        assert rep.steps == 6 and rep.evictions > 0
+    # weights, importance and kept lists are bit-identical to the one-workgroup form; outputs within tolerance
+    wl = W.Workload("t_split_same", 82, b=2, h=4, d=128, dtype="f16", prompt_lo=700, prompt_hi=3000, steps=5, w=32,
+                    sparsity_bp=9000, hh_frac=0.01)
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    states = []
+    for flags in (0, B.SWA_SPLIT_ROWS):
+        st = LS.new_state(wl, dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone()))
+        st.params.flags = flags
+        st.workspace = torch.zeros((B.swa_workspace_bytes(st.params),), dtype=torch.uint8, device="cuda")
+        B.swa_workspace_init(st.params, st.workspace)
+        st.score.zero_()
+        states.append(st)
+    for t in range(wl.steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        for st in states:
+            st.seq_len += 1
+            st.decode_step(q, kn, vn)
+        a, b_ = states
+        assert torch.equal(a.cache_len, b_.cache_len) and torch.equal(a.kept_cnt, b_.kept_cnt)
+        for s_i, L in enumerate(a.cache_len.tolist()):
+            c = int(a.kept_cnt[s_i])
+            assert torch.equal(a.probs[s_i, :, :L], b_.probs[s_i, :, :L]), f"step {t}: weights"
+            assert torch.equal(a.score[s_i, :, :L], b_.score[s_i, :, :L]), f"step {t}: importance"
+            assert torch.equal(a.kept_idx[s_i, :, :c], b_.kept_idx[s_i, :, :c]), f"step {t}: kept list"
+        assert float((a.out.float() - b_.out.float()).abs().max()) <= 2e-3
+        if t % 2 == 1:
+            for st in states:
+                st.compact()
+    # a full cache: the sequence is skipped by all four launches and reported
+    b, h, d, cap = 2, 2, 128, 512
+    params = B.make_params(b, h, d, cap, 4, 5000, torch.float16, flags=B.SWA_SPLIT_ROWS)
+    st = B.DecodeState(params)
+    st.K.normal_()
+    st.V.normal_()
+    st.cache_len.copy_(torch.tensor([512, 400], dtype=torch.int32))
+    st.seq_len.copy_(torch.tensor([513, 401], dtype=torch.int32))
+    st.out.fill_(7.0)
+    st.kept_cnt.fill_(-7)
+    x = torch.randn((b, h, d), device="cuda").half()
+    st.decode_step(x, x, x)
+    assert st.check_status() == B.SWA_ERR_CAPACITY
+    assert st.cache_len.tolist() == [512, 401] and st.kept_cnt[0].item() == -7
+    assert bool((st.out[0] == 7.0).all()) and not bool((st.out[1] == 7.0).any())
+
+
 def test_c3_opt13b_full_size_sampled_pairs(env):
     O, B, W, LS = env
     wl = W.CONFIGS["c3_opt13b"]
