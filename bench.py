@@ -4,18 +4,26 @@
 A "step" is one pass of the whole hot path over one batch: append, scores,
 softmax, importance accumulation, selection, sparse output and in-place
 compaction, for all b*h (sequence, head) pairs of one layer.  By default that is
-ONE kernel (swa_decode_step with SWA_FUSE_COMPACTION); --step-mode split runs
-swa_decode_step followed by swa_compact_kv instead.
+ONE kernel (swa_decode_step with SWA_FUSE_COMPACTION | SWA_UNORDERED); --step-mode
+fused keeps the cache in token order, --step-mode split runs swa_decode_step
+followed by swa_compact_kv.
 
-The timed region walks the workload's decode trajectory from the prompt on
-(first step right after the prompt, then the steady state with compaction every
-step).  To keep the data HBM-cold the way a multi-layer model does, R
-independent replicas of the layer state are stepped round-robin (replica = one
-layer's cache): step i works on replica i % R at trajectory step i // R.  R
+The job is the workload's decode trajectory from the prompt on (the step right
+after the prompt, which evicts most of the prompt, then the steady state with
+compaction every step).  To keep the data HBM-cold the way a multi-layer model
+does, R independent replicas of the layer state are stepped round-robin (replica
+= one layer's cache): step i works on replica i % R at trajectory step i // R.  R
 follows from BYTES, never from --steps: the R consecutive steps of one sweep
 must touch at least SWEEP_MIN_BYTES of distinct cache (four times the 256 MB
 Infinity Cache), and R >= 2.  Inputs are resident in HBM before the timed
 region starts.
+
+Without --steps the timed region is whole trajectories on every replica (the
+step after the prompt at its true weight, 1 of 512).  With --steps K --warmup W
+the schedule's first W steps run untimed and the next K are timed: a short
+stretch of the steady state (W >= R puts every replica's step after the prompt
+into the warm-up); the whole-trajectory figures, with the first step's own rate,
+are printed beside it in `whole_trajectory`.
 
 Prints ONE JSON line (see README / DESIGN for the fields).
 """
@@ -65,16 +73,19 @@ def torch_zeros(shape, device):
 class Replica:
     """One layer's device state plus the per-step logical lengths."""
 
-    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused, kv_int8=False, compact_every=1):
+    def __init__(self, B, W, wl, prompt, torch, len_bounds, fused, kv_int8=False, compact_every=1, split_rows=False):
         self.compact_every = compact_every
         self.fused = bool(fused)
         flags = {False: 0, True: B.SWA_FUSE_COMPACTION, "fused": B.SWA_FUSE_COMPACTION, "split": 0,
                  "unordered": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED,
                  "shared": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED | B.SWA_HEAD_SHARED,
                  "window": B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED}[fused]
+        if split_rows:
+            assert flags == 0, "SWA_SPLIT_ROWS goes with the two-call form"
+            flags = B.SWA_SPLIT_ROWS
         self.window_rows = min(max(wl.w, 1), B.SWA_MAX_WINDOW_ROWS) if fused == "window" else 0
         self.ring = None
-        self.fused = flags != 0
+        self.fused = (flags & B.SWA_FUSE_COMPACTION) != 0
         params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, flags=flags)
         st = B.DecodeState(params, device="cuda", debug_probs=False)
         st.K.copy_(prompt["K"])
@@ -157,7 +168,7 @@ def replicas_for(step_bytes):
 
 
 def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel_times=True, kv_int8=False,
-                   compact_every=1):
+                   compact_every=1, split_rows=False):
     """Times `steps` decode steps (None = whole trajectories on every replica) after `warmup` untimed ones."""
     dev = "cuda"
     T = wl.steps
@@ -174,28 +185,35 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
 
     step_bytes = [sum(wl.h * abp(m, k) for m, k in zip(ms[t], keeps[t])) for t in range(T)]
     R = replicas_for(step_bytes)
-    if steps is None:
-        steps = T * R
-    steps = min(steps, T * R)                 # a trajectory has T steps; more would need more replicas
-    warmup = min(warmup, T * R)
+    whole = steps is None
+    if whole:
+        # whole trajectories, from the prompt on, on every replica; the warm-up runs on replicas of its own
+        steps, start = T * R, 0
+        warmup = min(warmup, T * R)
+    else:
+        # one continuous job: the `warmup` untimed steps are the FIRST steps of the same round-robin schedule
+        # (they hold the step after the prompt of every replica once warmup >= R), the timed steps follow them
+        steps = min(steps, T * R)             # a trajectory has T steps; more would need more replicas
+        start = max(0, min(warmup, T * R - steps))
+        warmup = start
+    stop = start + steps
 
     def fresh(n):
-        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8, compact_every) for _ in range(n)]
+        reps = [Replica(B, W, wl, prompt, torch, len_bounds, fused, kv_int8, compact_every, split_rows) for _ in range(n)]
         for r in reps:
             r.finish_prompt(q_tail)
         return reps
 
-    def run(reps, count):
+    def run(reps, lo, hi):
         n = len(reps)
-        for i in range(count):
+        for i in range(lo, hi):
             t, r = divmod(i, n)
             q, kn, vn = inputs[t]
             reps[r].step(B, t, q, kn, vn)
 
-    # -------- warm-up: the first `warmup` steps of the same schedule, on replicas of their own
-    if warmup > 0:
+    if whole and warmup > 0:
         wreps = fresh(min(R, warmup))          # fewer steps than replicas: every one is a first step
-        run(wreps, warmup)
+        run(wreps, 0, warmup)
         torch.cuda.synchronize()
         del wreps
 
@@ -228,12 +246,13 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
 
     # -------- timed region: exactly `steps` steps
     reps = fresh(R)
+    run(reps, 0, start)                        # untimed: the schedule's first steps
     torch.cuda.synchronize()
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     if mode == "graph":
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
-            run(reps, steps)
+            run(reps, start, stop)
         torch.cuda.synchronize()
         t_wall0 = time.perf_counter()
         e0.record()
@@ -245,7 +264,7 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     else:
         t_wall0 = time.perf_counter()
         e0.record()
-        run(reps, steps)
+        run(reps, start, stop)
         e1.record()
         torch.cuda.synchronize()
         t_wall1 = time.perf_counter()
@@ -256,14 +275,16 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
     del reps
 
     # -------- accounting
-    kv_tokens = sum(sum(ms[i // R]) for i in range(steps))
-    alg_bytes = sum(step_bytes[i // R] for i in range(steps))
-    sweep = [step_bytes[i // R] for i in range(steps)]
+    timed = range(start, stop)
+    kv_tokens = sum(sum(ms[i // R]) for i in timed)
+    alg_bytes = sum(step_bytes[i // R] for i in timed)
+    sweep = [step_bytes[i // R] for i in timed]
     min_sweep = min(sum(sweep[j:j + R]) for j in range(0, max(1, steps - R + 1)))
 
     res = {
         "workload": wl.name, "steps": steps, "warmup": warmup, "replicas": R, "mode": mode, "fused": fused,
-        "trajectory_steps_covered": (steps + R - 1) // R, "min_sweep_bytes": min_sweep,
+        "trajectory_steps": [start // R, (stop - 1) // R], "first_step_timed": start < R,
+        "min_sweep_bytes": min_sweep,
         "cold": bool(min_sweep >= 2 * (256 << 20) or steps < R),
         "ms_per_step": total_ms / steps, "total_ms": total_ms, "host_wall_ms": wall_ms,
         "kv_tokens_per_s": kv_tokens / (total_ms * 1e-3),
@@ -284,9 +305,9 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
             b_.record()
         torch.cuda.synchronize()
         empty_ms = sorted(a.elapsed_time(b_) for a, b_ in pairs)[len(pairs) // 2]
-        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+        ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(stop)]
         n = len(reps)
-        for i in range(steps):
+        for i in range(stop):                  # the untimed first steps too: they hold the step after the prompt
             t, r = divmod(i, n)
             q, kn, vn = inputs[t]
             ev[i][0].record()
@@ -297,17 +318,17 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         torch.cuda.synchronize()
         dec = [max(0.0, e[0].elapsed_time(e[1]) - empty_ms) for e in ev]
         cmp_ = [max(0.0, e[1].elapsed_time(e[2]) - empty_ms) if not fused else 0.0 for e in ev]
-        res["decode_kernel_ms_avg"] = sum(dec) / steps
-        res["compact_kernel_ms_avg"] = sum(cmp_) / steps
+        res["decode_kernel_ms_avg"] = sum(dec[start:stop]) / steps
+        res["compact_kernel_ms_avg"] = sum(cmp_[start:stop]) / steps
         res["event_pair_overhead_ms"] = empty_ms
-        first = [dec[i] for i in range(steps) if i // n == 0]
-        steady = [dec[i] for i in range(steps) if i // n > 0]
+        first = [dec[i] for i in range(stop) if i // n == 0]
+        steady = [dec[i] for i in timed if i // n > 0]
         res["decode_first_step_ms"] = sum(first) / max(1, len(first))
         res["decode_steady_ms"] = sum(steady) / max(1, len(steady)) if steady else None
         res["decode_first_step_gbs"] = step_bytes[0] / (res["decode_first_step_ms"] * 1e-3) / 1e9
         res["decode_steady_gbs"] = None
         if steady:
-            sb = [step_bytes[i // n] for i in range(steps) if i // n > 0]
+            sb = [step_bytes[i // n] for i in timed if i // n > 0]
             res["decode_steady_gbs"] = sum(sb) / (sum(steady) * 1e-3) / 1e9
         del reps
     torch.cuda.empty_cache()
@@ -472,8 +493,9 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=None,
-                    help="timed steps of the headline workload, taken from the prompt on (default: whole "
-                         "trajectories on every replica)")
+                    help="timed steps of the headline workload; they follow the --warmup untimed steps of the same "
+                         "round-robin schedule, which starts at the prompt (default: whole trajectories on every "
+                         "replica, from the prompt on)")
     ap.add_argument("--warmup", type=int, default=None)
     ap.add_argument("--config", default=HEADLINE)
     ap.add_argument("--mode", choices=["graph", "stream"], default="graph")
@@ -490,6 +512,9 @@ def main():
     ap.add_argument("--compact-every", type=int, default=1,
                     help="with --step-mode split: call swa_compact_kv only every C-th step (0 = never); between "
                          "compactions the cache keeps every token and the selection runs over all of them")
+    ap.add_argument("--split-rows", action="store_true",
+                    help="with --step-mode split: SWA_SPLIT_ROWS, the rows of a pair spread over several workgroups "
+                         "(for few pairs with long caches, e.g. --compact-every 0)")
     ap.add_argument("--prefill-attention", action="store_true",
                     help="also time swa_prefill_attention over the workload's prompts")
     ap.add_argument("--no-cpu-baseline", action="store_true")
@@ -516,18 +541,21 @@ def main():
     torch.cuda.set_device(0)
     B.swa_prepare()                      # LDS limits raised before anything is captured
 
-    wl = W.CONFIGS[args.config]
+    wl = W.CONFIGS.get(args.config) or W.EXTRA[args.config]
     warmup = args.warmup if args.warmup is not None else 8
     fused_of = lambda sm: sm if sm != "split" else False
     if args.compact_every != 1 and args.step_mode != "split":
         print("bench.py: --compact-every needs --step-mode split (the fused forms compact every step)", file=sys.stderr)
         sys.exit(2)
+    if args.split_rows and (args.step_mode != "split" or args.kv_int8):
+        print("bench.py: --split-rows needs --step-mode split and the uncompressed cache", file=sys.stderr)
+        sys.exit(2)
     none = ("", "none")
     extra_forms = [x for x in args.ordered_forms.split(",") if x not in none and x != args.step_mode]
-    if args.compact_every != 1 or args.step_mode in ("shared", "window"):
+    if args.compact_every != 1 or args.split_rows or args.step_mode in ("shared", "window"):
         extra_forms = []
     res = bench_workload(wl, args.steps, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
-                         kv_int8=args.kv_int8, compact_every=args.compact_every)
+                         kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
     steps = res["steps"]
     roof = roofline_of(res, args.step_mode, args.kv_int8, wl.name)
     line = {
@@ -541,12 +569,18 @@ def main():
         "config": {"workload": wl.name, "b": wl.b, "h": wl.h, "d": wl.d, "prompt": [wl.prompt_lo, wl.prompt_hi],
                    "decode_steps_per_trajectory": wl.steps, "w": wl.w, "sparsity_bp": wl.sparsity_bp,
                    "replicas": res["replicas"], "cold": res["cold"], "min_sweep_bytes": res["min_sweep_bytes"],
-                   "timed": f"trajectory steps 0..{res['trajectory_steps_covered'] - 1} (from the prompt on) of "
-                            f"{res['replicas']} replicas, round-robin",
+                   "timed": f"steps {res['trajectory_steps'][0]}..{res['trajectory_steps'][1]} of the decode trajectories of "
+                            f"{res['replicas']} replicas stepped round-robin"
+                            + ("; from the prompt on" if res["first_step_timed"] else
+                               f"; the {res['warmup']} untimed warm-up steps are the first steps of the same schedule and "
+                               "hold every replica's step after the prompt, which whole_trajectory and "
+                               "roofline.first_step_frac report"),
                    "launch": args.mode, "compact_every": args.compact_every,
                    "step": STEP_TEXT[args.step_mode]
                            + ("; 8-bit compressed cache (swa_quantize_kv once, then swa_decode_step_q8)"
-                              if args.kv_int8 else "")},
+                              if args.kv_int8 else "")
+                           + ("; SWA_SPLIT_ROWS (a pair's rows over several workgroups, four launches)"
+                              if args.split_rows else "")},
         "roofline": roof,
         "whole_step_alg_gbs": res["alg_gbs_whole_step"],
         "generated_tokens_per_s": res["generated_tokens_per_s"],
@@ -573,11 +607,11 @@ def main():
     if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
 
-    # --steps covers only the first steps of the trajectory (the step after the prompt weighs 1/replicas
-    # of them): the same workload over whole trajectories, for reference
+    # --steps covers a short stretch of the trajectory: the same workload over whole trajectories (the step
+    # after the prompt included, at its true weight), for reference
     if args.steps is not None and not args.no_whole_trajectory and res["steps"] < wl.steps * res["replicas"]:
         r = bench_workload(wl, None, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
-                           kv_int8=args.kv_int8, compact_every=args.compact_every)
+                           kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
         line["whole_trajectory"] = summary_of(r, args.step_mode, args.kv_int8, wl.name)
 
     # the same workload in the forms that keep the cache in token order
@@ -599,7 +633,7 @@ def main():
         entry = {"workload": name}
         for sm in [args.step_mode] + extra_forms:
             r = bench_workload(o, None, min(o.steps, 8), args.mode, torch, B, W, fused=fused_of(sm),
-                               kv_int8=args.kv_int8, compact_every=args.compact_every)
+                               kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
             sm_sum = summary_of(r, sm, args.kv_int8, name)
             if sm == args.step_mode:
                 entry.update(sm_sum)

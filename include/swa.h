@@ -155,8 +155,8 @@ int swa_prepare(void);
  * partial outputs over slices of the kept list; their sum) and needs the larger workspace that
  * swa_workspace_bytes reports for this flag.  Attention weights, importance and the kept set are
  * bit-identical to the one-workgroup form; the output's partial sums are added in another order.
- * With many pairs or short caches (fewer than 256 rows per pair, or 1024 pairs and more) the call
- * falls back to the one-workgroup kernel.
+ * With many pairs or short caches (more than 128 pairs, or a length bound below 2048 rows: there the
+ * extra launches cost more than the slices gain) the call runs the one-workgroup kernel.
  */
 #define SWA_SPLIT_ROWS 16
 

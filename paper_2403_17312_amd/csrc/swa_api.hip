@@ -37,6 +37,10 @@ size_t shared_workspace_offset(const swa_params& p)
 
 int split_factor(int64_t pairs, int len_bound)
 {
+    // Four launches instead of one pay only when one workgroup per pair leaves most CUs idle for long:
+    // measured break-even near 128 pairs of 4096 rows; below 2048 rows the extra launches cost more
+    // than the slices gain.
+    if (pairs > 128 || len_bound < 2048) return 1;
     // enough workgroups to put about four on every CU, every slice at least 128 rows long
     int64_t g = (1024 + pairs - 1) / pairs;
     const int by_rows = len_bound / 128;

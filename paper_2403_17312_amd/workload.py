@@ -95,6 +95,13 @@ CONFIGS: Dict[str, Workload] = {
                                 hh_frac=0.01),
 }
 
+# Not one of the five: a single long-context sequence (32 heads, an 8192-token prompt), the shape for which the
+# rows of a pair are spread over several workgroups (few pairs, long caches).
+EXTRA: Dict[str, Workload] = {
+    "x_long_context_b1": Workload("x_long_context_b1", 6, b=1, h=32, d=128, dtype="f16", prompt_lo=8192,
+                                  prompt_hi=8192, steps=32, w=64, sparsity_bp=8000, hh_frac=0.01),
+}
+
 
 def _gen(device, *key: int) -> torch.Generator:
     g = torch.Generator(device=device)

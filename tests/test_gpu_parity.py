@@ -293,8 +293,8 @@ def test_strict_window_on_the_compressed_cache_and_with_the_head_reduced_set(env
 def test_rows_split_over_workgroups_matches_the_oracle_and_the_one_workgroup_form(env):
     # SWA_SPLIT_ROWS: few pairs with long caches; the step runs as four launches
     O, B, W, LS = env
-    for dtype, d, b, h, hi, ce in [("f16", 128, 1, 4, 2500, 0), ("bf16", 128, 2, 2, 1800, 3), ("f32", 64, 1, 3, 1500, 1),
-                                   ("f16", 64, 2, 3, 900, 0), ("bf16", 64, 1, 1, 5000, 2)]:
+    for dtype, d, b, h, hi, ce in [("f16", 128, 1, 4, 2500, 0), ("bf16", 128, 2, 2, 2300, 3), ("f32", 64, 1, 3, 2100, 1),
+                                   ("f16", 64, 2, 3, 900, 0), ("bf16", 64, 1, 1, 5000, 2)]:   # 900: the one-workgroup fall-back
         wl = W.Workload(f"t_split_{dtype}_{d}", 81, b=b, h=h, d=d, dtype=dtype, prompt_lo=hi // 2, prompt_hi=hi, steps=6,
                         w=16, sparsity_bp=8000, hh_frac=0.01, prefill_R=8)
         _say(f"  split rows: {dtype} d={d} b={b} h={h} prompts {hi // 2}..{hi}, compaction every {ce}")
