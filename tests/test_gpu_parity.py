@@ -738,6 +738,111 @@ def test_randomised_small_workloads_in_every_form(env):
                             kv_int8=form.startswith("q8"), sparsity_of_step=sp)
 
 
+@pytest.mark.parametrize("form", ["two-call", "unordered", "q8", "window"])
+def test_a_trajectory_resumed_from_a_saved_state_continues_bit_for_bit(env, form):
+    # stop after a few steps, copy the state tensors the header names (cache, importance, positions,
+    # lengths; the compression parameters; the ring) to the host, rebuild them in fresh device buffers
+    # whose unused slots hold NaN / garbage, and go on: every later output and the final state must
+    # equal the uninterrupted run's bits.  Nothing else (workspace, kept list, LDS) carries state.
+    O, B, W, LS = env
+    wl = W.Workload("t_resume", 47, b=3, h=5, d=128, dtype="f16", prompt_lo=90, prompt_hi=260, steps=12, w=8,
+                    sparsity_bp=7500, hh_frac=0.02)
+    fused = form != "two-call"
+    flags = (B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED) if fused else 0
+    R = 6
+    prompt = W.make_prompt(wl, "cuda")
+    inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(wl.steps)]
+    seq_lens = [(prompt["cache_len"] + (t + 1)).to(torch.int32) for t in range(wl.steps)]
+
+    def fresh_state(src=None):
+        params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype, flags=flags)
+        st = B.DecodeState(params, debug_probs=False)
+        ring = torch.zeros((wl.b, wl.h, R, wl.cap), device="cuda")
+        if src is None:
+            st.K.copy_(prompt["K"])
+            st.V.copy_(prompt["V"])
+            st.pos.copy_(prompt["pos"])
+            st.cache_len.copy_(prompt["cache_len"])
+            if form == "q8":
+                st.quantize()
+        else:
+            saved, L = src
+            if form == "q8":
+                st.quantize()                       # allocates the code tensors and the parameter array
+                st.qparams.copy_(saved["qparams"].cuda())
+            st.K.view(torch.uint8).fill_(0xFF)      # NaN in fp16, code 255: unused slots must never be read
+            st.V.view(torch.uint8).fill_(0xFF)
+            st.score.fill_(float("nan"))
+            st.pos.fill_(-7)
+            ring.fill_(float("nan"))
+            for s_i in range(wl.b):
+                n = L[s_i]
+                st.K[s_i, :, :n].copy_(saved["K"][s_i, :, :n].cuda())
+                st.V[s_i, :, :n].copy_(saved["V"][s_i, :, :n].cuda())
+                st.score[s_i, :, :n].copy_(saved["score"][s_i, :, :n].cuda())
+                st.pos[s_i, :, :n].copy_(saved["pos"][s_i, :, :n].cuda())
+                ring[s_i, :, :, :n].copy_(saved["ring"][s_i, :, :, :n].cuda())
+            st.cache_len.copy_(torch.tensor(L, dtype=torch.int32))
+        return st, ring
+
+    def run(st, ring, t0, t1, outs):
+        cur, nxt = st.cache_len, st.kept_cnt
+        for t in range(t0, t1):
+            q, kn, vn = inputs[t]
+            kidx = None if fused else st.kept_idx
+            if form == "window":
+                B.swa_decode_step_window(st.params, q, kn, vn, st.K, st.V, ring, R, t % R, st.score, st.pos, cur,
+                                         seq_lens[t], kidx, nxt, st.out, None, st.workspace)
+            elif form == "q8":
+                B.swa_decode_step_q8(st.params, q, kn, vn, st.K, st.V, st.qparams, st.score, st.pos, cur, seq_lens[t],
+                                     kidx, nxt, st.out, None, st.workspace)
+            else:
+                B.swa_decode_step(st.params, q, kn, vn, st.K, st.V, st.score, st.pos, cur, seq_lens[t], kidx, nxt,
+                                  st.out, None, st.workspace)
+            outs.append(st.out.clone())
+            if fused:
+                cur, nxt = nxt, cur
+            else:
+                B.swa_compact_kv(st.params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt, st.cache_len,
+                                 st.workspace)
+        return cur
+
+    def valid(st, ring, lens_t):
+        L = lens_t.tolist()
+        host = lambda x: x.cpu()
+        return ({"K": host(st.K), "V": host(st.V), "score": host(st.score), "pos": host(st.pos), "ring": host(ring),
+                 "qparams": host(st.qparams) if form == "q8" else None}, L)
+
+    def same(a, b_, L):
+        for name in ("K", "V", "score", "pos"):
+            for s_i in range(wl.b):
+                x, y = a[name][s_i, :, :L[s_i]], b_[name][s_i, :, :L[s_i]]
+                assert torch.equal(x.view(torch.uint8), y.view(torch.uint8)), f"{form}: {name} of sequence {s_i}"
+        if form == "window":
+            for s_i in range(wl.b):
+                assert torch.equal(a["ring"][s_i, :, :, :L[s_i]], b_["ring"][s_i, :, :, :L[s_i]]), f"{form}: ring"
+
+    stop = 5
+    st, ring = fresh_state()
+    outs_a = []
+    lens_a = run(st, ring, 0, wl.steps, outs_a)
+    final_a = valid(st, ring, lens_a)
+    st2, ring2 = fresh_state()
+    outs_b = []
+    mid = valid(st2, ring2, run(st2, ring2, 0, stop, outs_b))
+    del st2, ring2
+    st3, ring3 = fresh_state(mid)
+    lens_c = run(st3, ring3, stop, wl.steps, outs_b)
+    final_c = valid(st3, ring3, lens_c)
+    assert final_a[1] == final_c[1], f"{form}: lengths {final_a[1]} vs {final_c[1]}"
+    assert len(outs_a) == len(outs_b) == wl.steps
+    for t in range(wl.steps):
+        assert torch.equal(outs_a[t], outs_b[t]), f"{form}: output of step {t}"
+    same(final_a[0], final_c[0], final_a[1])
+    for x in (st, st3):
+        assert x.check_status() == 0
+
+
 @pytest.mark.parametrize("form", ["unordered", "fused", "shared", "q8", "window"])
 def test_hip_graph_replays_equal_the_eager_run(env, form):
     # bench.py times HIP-graph replays: a captured trajectory, replayed several times with the
