@@ -37,9 +37,6 @@
 //   * the strict local attention sum (importance = sum of a ring of the last R attention rows,
 //     whose columns follow their tokens through the compaction).
 #include "swa_kernels.hpp"
-#ifndef SWA_UF
-#define SWA_UF 2
-#endif
 
 namespace swa {
 
@@ -133,7 +130,7 @@ swa_decode_kernel(DecodeArgs a)
     constexpr int XROWB = D * Elem<AT>::kBytes;        // one row of q, k_new, v_new, out
     constexpr bool kQ8 = Elem<T>::kBytes == 1;
     constexpr int UK = 8;                   // key rows in flight per group (key-only pass)
-    constexpr int UF = SWA_UF;              // key+value row pairs per group and pipeline stage (fused pass)
+    constexpr int UF = 2;                   // key+value row pairs per group and pipeline stage (fused pass)
     // The 512-thread instantiation (long caches: the step after a prompt) has 128 registers per
     // lane and keeps twice as many rows in flight in the gathered pass and in the row moves.
     constexpr bool kWide = NT >= 512;

@@ -105,22 +105,15 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
 
     // Unconditional tile load (rows past the end re-read the last row and are masked later), so
     // that the loads of the next tile can stay in flight while the current one is reduced.
-#ifndef SWA_PF_NT1
-#define SWA_PF_NT1 0
-#endif
-#ifndef SWA_PF_NT2
-#define SWA_PF_NT2 0
-#endif
-#ifndef SWA_PF_REV
-#define SWA_PF_REV 1
-#endif
-    auto load_tile = [&](int tile, Vec16(&kv)[NV], bool nt) {
+    // Plain loads, not streaming ones: a lane takes 32 bytes of a line per instruction, so the line
+    // has to survive in the cache between the instructions that consume it.
+    auto load_tile = [&](int tile, Vec16(&kv)[NV]) {
         int krow = tile * 32 + l32;
         krow = krow < s ? krow : s - 1;
         krow = krow < 0 ? 0 : krow;
         const char* src = Kp + (int64_t)krow * ROWB + lane_off;
 #pragma unroll
-        for (int v = 0; v < NV; ++v) kv[v] = nt ? load16_stream(src + v * 32) : load16(src + v * 32);
+        for (int v = 0; v < NV; ++v) kv[v] = load16(src + v * 32);
     };
 
     // ------------------------------ pass 1: row statistics ------------------------------
@@ -160,11 +153,11 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     };
     {
         Vec16 kA[NV], kB[NV];
-        load_tile(wave, kA, SWA_PF_NT1);
+        load_tile(wave, kA);
         for (int tile = wave; tile < ntiles; tile += 2 * NW) {
-            load_tile(tile + NW, kB, SWA_PF_NT1);
+            load_tile(tile + NW, kB);
             stats_tile(tile, kA);
-            load_tile(tile + 2 * NW, kA, SWA_PF_NT1);
+            load_tile(tile + 2 * NW, kA);
             if (tile + NW < ntiles) stats_tile(tile + NW, kB);
         }
     }
@@ -223,25 +216,15 @@ __global__ void __launch_bounds__(256) swa_prefill_kernel(PrefillArgs a)
     };
     {
         Vec16 kA[NV], kB[NV];
-#if SWA_PF_REV
         // the keys read last by pass 1 are read first here
         const int last = ntiles - 1 - wave;
-        load_tile(last, kA, SWA_PF_NT2);
+        load_tile(last, kA);
         for (int tile = last; tile >= 0; tile -= 2 * NW) {
-            load_tile(tile - NW, kB, SWA_PF_NT2);
+            load_tile(tile - NW, kB);
             colsum_tile(tile, kA);
-            load_tile(tile - 2 * NW, kA, SWA_PF_NT2);
+            load_tile(tile - 2 * NW, kA);
             if (tile - NW >= 0) colsum_tile(tile - NW, kB);
         }
-#else
-        load_tile(wave, kA, SWA_PF_NT2);
-        for (int tile = wave; tile < ntiles; tile += 2 * NW) {
-            load_tile(tile + NW, kB, SWA_PF_NT2);
-            colsum_tile(tile, kA);
-            load_tile(tile + 2 * NW, kA, SWA_PF_NT2);
-            if (tile + NW < ntiles) colsum_tile(tile + NW, kB);
-        }
-#endif
     }
     if (Sp)
         for (int j = s + tid; j < cap; j += NT) Sp[j] = 0.f;
