@@ -364,6 +364,25 @@ def bench_prefill_attention(wl, torch, B, W):
             "note": "dense causal attention over the prompts + importance seed, one call"}
 
 
+def prewarm(torch, B, seconds):
+    """Keeps the GPU streaming for `seconds` before anything is timed (clocks and power state settle over a
+    much longer time than a few warm-up steps last).  Untimed, and nothing of the workload is touched."""
+    if seconds <= 0:
+        return 0
+    x = torch.ones((1 << 28,), dtype=torch.float32, device="cuda")        # 1 GiB
+    sink = torch.zeros((1,), dtype=torch.int32, device="cuda")
+    t0 = time.perf_counter()
+    n = 0
+    while time.perf_counter() - t0 < seconds:
+        for _ in range(16):
+            B.swa_probe_stream_read(x, x.numel() * 4, sink)
+        torch.cuda.synchronize()
+        n += 16
+    del x
+    torch.cuda.empty_cache()
+    return n
+
+
 def stream_read_ceiling(torch, B):
     """Streaming-read rate of this GPU on a 4 GiB buffer (plain 128-bit loads, nothing else)."""
     x = torch.ones((1 << 30,), dtype=torch.float32, device="cuda")
@@ -517,6 +536,8 @@ def main():
                          "(for few pairs with long caches, e.g. --compact-every 0)")
     ap.add_argument("--prefill-attention", action="store_true",
                     help="also time swa_prefill_attention over the workload's prompts")
+    ap.add_argument("--prewarm-s", type=float, default=1.5,
+                    help="seconds of plain streaming reads before anything is timed (0 = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -540,6 +561,7 @@ def main():
     B.lib()
     torch.cuda.set_device(0)
     B.swa_prepare()                      # LDS limits raised before anything is captured
+    prewarm(torch, B, args.prewarm_s)
 
     wl = W.CONFIGS.get(args.config) or W.EXTRA[args.config]
     warmup = args.warmup if args.warmup is not None else 8
