@@ -244,31 +244,46 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         quantize_ms = e0.elapsed_time(e1)
         del tmp, ck, cv, qp
 
-    # -------- timed region: exactly `steps` steps
+    # -------- timed region: exactly `steps` steps; an event between the steps right after a prompt (the first
+    # R of the schedule) and the steady ones splits the time without bracketing single launches
     reps = fresh(R)
     run(reps, 0, start)                        # untimed: the schedule's first steps
     torch.cuda.synchronize()
-    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    split = min(max(start, R), stop)
+    e0, em, e1 = (torch.cuda.Event(enable_timing=True) for _ in range(3))
     if mode == "graph":
-        g = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(g):
-            run(reps, start, stop)
+        graphs = []
+        for lo, hi in ((start, split), (split, stop)):
+            if hi > lo:
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    run(reps, lo, hi)
+                graphs.append((lo, g))
         torch.cuda.synchronize()
         t_wall0 = time.perf_counter()
         e0.record()
-        g.replay()
+        for lo, g in graphs:
+            if lo == split:
+                em.record()
+            g.replay()
+        if split == stop:
+            em.record()
         e1.record()
         torch.cuda.synchronize()
         t_wall1 = time.perf_counter()
-        del g
+        del graphs
     else:
         t_wall0 = time.perf_counter()
         e0.record()
-        run(reps, start, stop)
+        run(reps, start, split)
+        em.record()
+        run(reps, split, stop)
         e1.record()
         torch.cuda.synchronize()
         t_wall1 = time.perf_counter()
     total_ms = e0.elapsed_time(e1)
+    first_ms = e0.elapsed_time(em) / (split - start) if split > start else None
+    steady_ms = em.elapsed_time(e1) / (stop - split) if stop > split else None
     wall_ms = (t_wall1 - t_wall0) * 1e3
     for r in reps:
         assert r.st.check_status() == 0
@@ -292,6 +307,11 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
         "alg_bytes_per_step": alg_bytes / steps,
         "alg_gbs_whole_step": alg_bytes / (total_ms * 1e-3) / 1e9,
         "prefill_seed_ms": prefill_ms, "quantize_kv_ms": quantize_ms,
+        # whole steps (every launch of the step), from the event between the two stretches of the timed region
+        "first_step_ms": first_ms, "steady_step_ms": steady_ms,
+        "first_step_gbs": (step_bytes[0] / (first_ms * 1e-3) / 1e9) if first_ms else None,
+        "steady_step_gbs": (sum(step_bytes[i // R] for i in range(split, stop)) / (stop - split) / (steady_ms * 1e-3) / 1e9)
+                           if steady_ms else None,
     }
 
     # -------- per-kernel durations with HIP events on the launch stream (separate pass)
@@ -479,8 +499,12 @@ def roofline_of(res, step_mode, kv_int8, wl_name):
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
     tag = ("" if step_mode == "unordered" else "_" + step_mode) + ("_q8" if kv_int8 else "")
     traffic = load_traffic(wl_name + tag) if one_kernel else None
-    first_frac = res["decode_first_step_gbs"] / HBM_PEAK_GBS if res.get("decode_first_step_gbs") else None
-    steady_frac = res["decode_steady_gbs"] / HBM_PEAK_GBS if res.get("decode_steady_gbs") else None
+    # one-kernel forms: the step is the kernel, so the timed region's own split applies; two calls: the
+    # per-launch event brackets (which read a few microseconds low: an empty bracket costs more than a full one)
+    first_gbs = res.get("first_step_gbs") if one_kernel else res.get("decode_first_step_gbs")
+    steady_gbs = res.get("steady_step_gbs") if one_kernel else res.get("decode_steady_gbs")
+    first_frac = first_gbs / HBM_PEAK_GBS if first_gbs else None
+    steady_frac = steady_gbs / HBM_PEAK_GBS if steady_gbs else None
     return {
         "bound": "hbm", "kernel": "swa_decode_kernel",
         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
@@ -492,7 +516,7 @@ def roofline_of(res, step_mode, kv_int8, wl_name):
         "alg_bytes_per_launch": res["alg_bytes_per_step"], "avg_launch_ms": dec_ms,
         "timing": ("HIP events around the timed region on the launch stream / launches" if one_kernel
                    else "HIP events around every swa_decode_step launch"),
-        "first_step_gbs": res.get("decode_first_step_gbs"), "steady_gbs": res.get("decode_steady_gbs"),
+        "first_step_gbs": first_gbs, "steady_gbs": steady_gbs,
         "first_step_frac": first_frac, "steady_frac": steady_frac,
     }
 
@@ -608,7 +632,7 @@ def main():
         "generated_tokens_per_s": res["generated_tokens_per_s"],
         "detail": {k: res.get(k) for k in ("decode_kernel_ms_avg", "compact_kernel_ms_avg", "decode_first_step_ms",
                                            "decode_steady_ms", "event_pair_overhead_ms", "host_wall_ms",
-                                           "prefill_seed_ms", "quantize_kv_ms")},
+                                           "prefill_seed_ms", "quantize_kv_ms", "first_step_ms", "steady_step_ms")},
     }
     ceil_gbs = stream_read_ceiling(torch, B)
     line["roofline"]["measured_stream_read_gbs"] = ceil_gbs
@@ -635,6 +659,10 @@ def main():
         r = bench_workload(wl, None, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
                            kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
         line["whole_trajectory"] = summary_of(r, args.step_mode, args.kv_int8, wl.name)
+        if line["roofline"]["first_step_frac"] is None:      # the timed stretch held no step after a prompt
+            line["roofline"]["first_step_frac"] = line["whole_trajectory"]["roofline"]["first_step_frac"]
+            line["roofline"]["first_step_gbs"] = line["whole_trajectory"]["roofline"]["first_step_frac"] * HBM_PEAK_GBS
+            line["roofline"]["first_step_from"] = "whole_trajectory"
 
     # the same workload in the forms that keep the cache in token order
     forms = []
