@@ -1,7 +1,7 @@
 // Token-level offload tier: the store and load halves of the GPU-CPU caching phase of the
-// paper's dynamic scheduling (Section V-A, Algorithm 2: "GM -> CM.store" of the tokens that leave
-// GPU memory, "CM -> GM.load" of tokens that are needed again).  Tokens are moved one (sequence,
-// head) row at a time, never whole heads: that is the point of the paper's token-level scheduling.
+// paper's dynamic scheduling (Section V-A, Algorithm 2, Phase II: tokens that leave GPU memory are
+// stored in CPU memory, tokens that are needed again are loaded back).  Tokens are moved one
+// (sequence, head) row at a time, never whole heads: that is the point of token-level scheduling.
 //
 // The host store is pinned host memory that the device addresses directly; a workgroup copies its
 // pair's rows with 16-byte vector accesses, so a row crosses the bus as whole 256-byte bursts.
