@@ -287,7 +287,7 @@ static int decode_common(const swa_params* params, const void* q, const void* k_
                          void* k_cache, void* v_cache, const float* qparams, float* score, int32_t* pos,
                          int32_t* cache_len, const int32_t* seq_len, int32_t* kept_idx, int32_t* kept_cnt,
                          void* out, float* probs_dbg, void* workspace, void* stream, float* ring = nullptr,
-                         int32_t ring_rows = 0, int32_t ring_row = 0)
+                         int32_t ring_rows = 0, int32_t ring_row = 0, bool zero_arrival_counters = false)
 {
     const bool fuse = (params->flags & SWA_FUSE_COMPACTION) != 0;
     if (!q || !k_new || !v_new || !k_cache || !v_cache || !score || !pos || !cache_len || !seq_len ||
@@ -301,6 +301,14 @@ static int decode_common(const swa_params* params, const void* q, const void* k_
     if (!swa::aligned16(q) || !swa::aligned16(k_new) || !swa::aligned16(v_new) || !swa::aligned16(k_cache) ||
         !swa::aligned16(v_cache) || !swa::aligned16(out))
         return SWA_ERR_ALIGNMENT;
+    if (zero_arrival_counters) {
+        // A fill kernel, not a memset node: callers may capture this call into a graph.
+        hipLaunchKernelGGL(swa::swa_fill_zero_kernel, dim3((unsigned)((params->b + 255) / 256)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream),
+                           reinterpret_cast<int32_t*>(static_cast<char*>(workspace) + swa::kWsArriveOffset),
+                           (int64_t)params->b);
+        if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
+    }
     return swa::launch_decode(*params, swa::effective_scale(params), q, k_new, v_new, k_cache, v_cache, score,
                               pos, cache_len, seq_len, kept_idx, kept_cnt, out, probs_dbg, workspace, qparams, ring,
                               ring_rows, ring_row, static_cast<hipStream_t>(stream));
@@ -389,18 +397,11 @@ int swa_decode_step_static(const swa_params* params, const void* q, const void* 
     void* ptr = nullptr;
     rc = swa::static_scratch(&ptr);
     if (rc != SWA_OK) return rc;
-    if (!(params->flags & SWA_FUSE_COMPACTION)) {
-        // The arrival counters must start at zero whatever an earlier call (of another shape, or
-        // one that was abandoned) left there.  A fill kernel, not a memset node: callers may
-        // capture this call into a graph.  The sticky status word is left alone.
-        hipLaunchKernelGGL(swa::swa_fill_zero_kernel, dim3((unsigned)((params->b + 255) / 256)), dim3(256), 0,
-                           static_cast<hipStream_t>(stream),
-                           reinterpret_cast<int32_t*>(static_cast<char*>(ptr) + swa::kWsArriveOffset),
-                           (int64_t)params->b);
-        if (hipGetLastError() != hipSuccess) return SWA_ERR_HIP;
-    }
+    // The arrival counters of the two-call form must start at zero whatever an earlier call (of another
+    // shape, or one that was abandoned) left in the shared array; the sticky status word is left alone.
     return decode_common(params, q, k_new, v_new, k_cache, v_cache, nullptr, score, pos, cache_len, seq_len,
-                         kept_idx, kept_cnt, out, probs_dbg, ptr, stream);
+                         kept_idx, kept_cnt, out, probs_dbg, ptr, stream, nullptr, 0, 0,
+                         !(params->flags & SWA_FUSE_COMPACTION));
 }
 
 int swa_decode_step_q8(const swa_params* params, const void* q, const void* k_new, const void* v_new,
