@@ -51,6 +51,15 @@ def test_offload_then_reload_over_a_trajectory(env, dtype, d, q8):
     _trajectory(env, wl, q8)
 
 
+def test_offload_without_a_local_window_stores_the_newest_token_when_it_loses(env):
+    # w = 0: the token of the step is a candidate like the others and is usually evicted at once
+    O, OF, B, W, LS = env
+    wl = W.Workload("t_off_w0", 73, b=2, h=3, d=64, dtype="f16", prompt_lo=40, prompt_hi=90, steps=6, w=0,
+                    sparsity_bp=6000, hh_frac=0.02)
+    print("  offload tier: no local window", flush=True)
+    _trajectory(env, wl, False)
+
+
 def test_offload_at_full_size_every_pair(env):
     # config 2 at full size: the step after the prompt evicts about 410 of 513 tokens of each of the 512 pairs
     O, OF, B, W, LS = env

@@ -30,6 +30,7 @@ def test_no_token_is_lost_or_duplicated_over_a_trajectory(oracle):
     n = lens.copy()
     cl = lens.copy()
     new_rows = {}
+    score_at = {}
     for t in range(12):
         n = n + 1
         q, kn, vn = (rng.standard_normal((b, h, d)) for _ in range(3))
@@ -37,7 +38,16 @@ def test_no_token_is_lost_or_duplicated_over_a_trajectory(oracle):
             new_rows[(s, int(n[s]) - 1)] = (kn[s].copy(), vn[s].copy())
         kept, cnt, out, p = O.decode_step(q, kn, vn, K, V, score, pos, cl, n, w, sp, 0.5)
         before = store.len.copy()
+        # the importance every token has right now, by position: what a token evicted now must carry
+        for s in range(b):
+            for hd in range(h):
+                for i in range(int(cl[s])):
+                    score_at[(s, hd, int(pos[s, hd, i]))] = score[s, hd, i]
         assert OF.offload_evicted(K, V, score, pos, kept, cnt, cl, store) == []
+        for s in range(b):
+            for hd in range(h):
+                for j in range(int(before[s, hd]), int(store.len[s, hd])):
+                    assert store.score[s, hd, j] == score_at[(s, hd, int(store.pos[s, hd, j]))] > 0
         for s in range(b):
             assert np.all(store.len[s] - before[s] == cl[s] - cnt[s])          # exactly the evicted tokens
         O.compact(K, V, score, pos, kept, cnt, cl)
@@ -53,6 +63,27 @@ def test_no_token_is_lost_or_duplicated_over_a_trajectory(oracle):
     # the importance stored with a token is the value it had when it was evicted: never above the
     # smallest kept one at that time is not guaranteed later, but it is positive and finite
     assert np.all(np.isfinite(store.score)) and np.all(store.score >= 0)
+
+
+def test_the_newest_token_is_offloaded_too_when_it_loses(oracle):
+    # no local window (w = 0): the token of the current step is a candidate like any other, has the
+    # smallest importance (one attention weight against the others' sums) and is evicted at once
+    O = oracle
+    rng = np.random.default_rng(8)
+    b, h, cap, d = 1, 2, 16, 4
+    K, V, pos, lens = _state(rng, b, h, cap, d, [8])
+    score = np.full((b, h, cap), 5.0)
+    store = OF.HostStore(b, h, d, 8)
+    cl, n = lens.copy(), lens + 1
+    q, kn, vn = (rng.standard_normal((b, h, d)) for _ in range(3))
+    kept, cnt, out, p = O.decode_step(q, kn, vn, K, V, score, pos, cl, n, 0, 2000, 0.5)   # keeps 7 of 9
+    assert cnt[0] == 7 and cl[0] == 9
+    OF.offload_evicted(K, V, score, pos, kept, cnt, cl, store)
+    for hd in range(h):
+        assert store.len[0, hd] == 2 and 8 in store.pos[0, hd, :2].tolist()        # position 8 = the new token
+        j = store.pos[0, hd, :2].tolist().index(8)
+        assert np.array_equal(store.K[0, hd, j], kn[0, hd]) and np.array_equal(store.V[0, hd, j], vn[0, hd])
+        assert store.pos[0, hd, 0] < store.pos[0, hd, 1]                           # ascending slot order
 
 
 def test_a_full_store_skips_the_pair_and_writes_nothing(oracle):
