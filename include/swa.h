@@ -110,11 +110,12 @@ typedef struct {
  *   - kept_idx[j], when given, is the PRE-compaction slot of the token that ends in slot j.
  * pos must hold each slot's token position (it does after any sequence of calls that started
  * from a cache filled in token order with pos = 0..len-1).  Up to 7168 live slots.
- * The window rule assumes that the most recent min(w, m) tokens are all still cached, which holds
- * as long as the effective window grows by at most one token per step (always true for a fixed
- * w, and for SWA_W_EVEN_SPLIT at a fixed sparsity).  A caller that widens w, or lowers the
- * sparsity under SWA_W_EVEN_SPLIT, by more than that between two calls must use the ordered form
- * for that step: here the cache would then keep fewer than `keep` distinct live tokens.
+ * The most recent min(w, m) tokens are all still cached as long as the effective window grows by
+ * at most one token per step (always true for a fixed w, and for SWA_W_EVEN_SPLIT at a fixed
+ * sparsity).  If a caller widens it faster, some positions of the new window were evicted
+ * earlier: the step keeps every window token that is present and makes up the rest of the budget
+ * with global tokens, so the cache stays dense and holds exactly `keep` tokens.  (The ordered
+ * forms keep the most recent SLOTS instead; the two agree whenever no window position is missing.)
  */
 #define SWA_UNORDERED 2
 #define SWA_MAX_UNORDERED_SLOTS 7168

@@ -655,6 +655,24 @@ swa_decode_kernel(DecodeArgs a)
         } else {
             have_list = true;
             __syncthreads();   // keys of every thread are in LDS
+            if (bag) {
+                // The window is found by position.  If the caller widened it since the last call,
+                // some of its positions were evicted earlier: what is missing is made up by global
+                // tokens, so that exactly `keep` tokens are kept and every hole finds its mover.
+                int present = 0;
+                for (int base = 0; base < m; base += NT) {
+                    const int i = base + tid;
+                    present += (int)__popcll(__ballot(i < m && s_pos[i] >= wlo));
+                }
+                if (lane == 0) s_wcnt[0][wave] = present;
+                __syncthreads();
+                present = 0;
+#pragma unroll
+                for (int v = 0; v < NW; ++v) present += s_wcnt[0][v];
+                __syncthreads();
+                n_global = keep - present;
+                n_global = n_global < 0 ? 0 : n_global;
+            }
             // radix select: the n_global-th largest key among candidates 0..ncand-1
             uint32_t prefix = 0u, mask = 0u;
             int rem = n_global;

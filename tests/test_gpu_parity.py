@@ -161,6 +161,72 @@ def test_unordered_ties_go_to_the_earliest_token(env):
         LS.run_lockstep(wl, prompt=prompt, fused=True)
 
 
+def test_unordered_window_that_was_widened_keeps_exactly_the_budget(env):
+    # The unordered form finds the window by token position.  When the caller widens w (and tightens
+    # the budget) between two calls, some positions of the new window were evicted long ago: the step
+    # must still keep exactly `keep` tokens - every present window token, and the best of the others
+    # for the rest - and leave a dense cache whose rows are the kept tokens' rows.
+    O, B, W, LS = env
+    wl = W.Workload("t_un_grow", 37, b=3, h=4, d=128, dtype="f16", prompt_lo=60, prompt_hi=140, steps=12, w=4,
+                    sparsity_bp=5000, hh_frac=0.02)
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    st = LS.new_state(wl, prompt)
+    st.score.zero_()
+    st.params.flags = B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED
+    for t in range(wl.steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        st.decode_compact_step(q, kn, vn)
+    assert st.check_status() == 0
+    # the widened step: w 4 -> 24, sparsity 50 % -> 80 %
+    w2, sp2 = 24, 8000
+    lens = st.cache_len.cpu().numpy()
+    # a copy in the two-call form gives the weights and the new importance of every slot (same arithmetic)
+    ref = LS.new_state(wl, dict(prompt, K=st.K.clone(), V=st.V.clone(), pos=st.pos.clone()))
+    for name in ("score", "cache_len", "seq_len"):
+        getattr(ref, name).copy_(getattr(st, name))
+    ref.params.w, ref.params.sparsity_bp = w2, sp2
+    st.params.w, st.params.sparsity_bp = w2, sp2
+    q, kn, vn = W.make_step(wl, wl.steps, prompt["mu"])
+    ref.seq_len += 1
+    ref.decode_step(q, kn, vn)
+    st.seq_len += 1
+    st.decode_compact_step(q, kn, vn)
+    assert st.check_status() == 0
+    n = st.seq_len.cpu().numpy()
+    snew, probs = LS._np64(ref.score), LS._np64(ref.probs)
+    pos_all = ref.pos.cpu().numpy()                          # slot len holds the new token now
+    Kall, Vall = LS._np64(ref.K), LS._np64(ref.V)
+    got_len = st.cache_len.cpu().numpy()
+    gpos, gK, gV, gS = st.pos.cpu().numpy(), LS._np64(st.K), LS._np64(st.V), LS._np64(st.score)
+    out_g = LS._np64(st.out)
+    grew = 0
+    for s_i in range(wl.b):
+        m = int(lens[s_i]) + 1
+        keep, n_local, _ = O.budget(int(n[s_i]), m, w2, sp2)
+        assert got_len[s_i] == keep < m
+        wlo = int(n[s_i]) - n_local
+        for hd in range(wl.h):
+            p_ = pos_all[s_i, hd, :m]
+            window = [i for i in range(m) if p_[i] >= wlo]
+            grew += len(window) < n_local
+            others = sorted((i for i in range(m) if p_[i] < wlo), key=lambda i: (-snew[s_i, hd, i], p_[i]))
+            want = window + others[:keep - len(window)]
+            want_pos = sorted(int(p_[i]) for i in want)
+            got_pos = gpos[s_i, hd, :keep].tolist()
+            assert sorted(got_pos) == want_pos, f"pair {s_i},{hd}: kept tokens"
+            slot_of = {int(p_[i]): i for i in range(m)}
+            for j, tp in enumerate(got_pos):                # the rows in the compacted cache are those tokens' rows
+                i = slot_of[tp]
+                assert np.array_equal(gK[s_i, hd, j], Kall[s_i, hd, i]) and np.array_equal(gV[s_i, hd, j], Vall[s_i, hd, i])
+                assert gS[s_i, hd, j] == snew[s_i, hd, i]
+            idx = np.array(sorted(want), dtype=np.int32)[None, None, :]
+            out_o = O.sparse_attention(LS._np64(q[s_i:s_i + 1, hd:hd + 1]), Kall[s_i:s_i + 1, hd:hd + 1],
+                                       Vall[s_i:s_i + 1, hd:hd + 1], idx, np.array([keep], dtype=np.int32), wl.scale)
+            LS.check_out(out_g[s_i:s_i + 1, hd:hd + 1], out_o, wl.dtype, f"widened window, pair {s_i},{hd}")
+    assert grew > 0, "the case must contain windows with evicted positions"
+
+
 def test_even_split_of_algorithm_1_in_every_step_mode(env):
     # w = SWA_W_EVEN_SPLIT: k = nint(n r / 2) local and k global tokens, recomputed per sequence and step
     O, B, W, LS = env
