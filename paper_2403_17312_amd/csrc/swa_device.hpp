@@ -27,6 +27,7 @@ struct Q8 {};   // cache rows hold 8-bit codes (Section V-B); queries, new rows 
 typedef _Float16 half2_t __attribute__((ext_vector_type(2)));
 typedef _Float16 half8_t __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x8_t __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
 typedef float float4_t __attribute__((ext_vector_type(4)));
 typedef float float16_t __attribute__((ext_vector_type(16)));
 
@@ -177,18 +178,15 @@ struct QFrag<F16> {
 };
 template <>
 struct QFrag<BF16> {
-    float f[8];
-    __device__ __forceinline__ void load(const Vec16& v) { unpack<BF16>(v, f); }
+    Vec16 raw;
+    __device__ __forceinline__ void load(const Vec16& v) { raw = v; }
     __device__ __forceinline__ float dot(const Vec16& k, float acc) const
     {
-        acc = __builtin_fmaf(bf16_lo(k.x), f[0], acc);
-        acc = __builtin_fmaf(bf16_hi(k.x), f[1], acc);
-        acc = __builtin_fmaf(bf16_lo(k.y), f[2], acc);
-        acc = __builtin_fmaf(bf16_hi(k.y), f[3], acc);
-        acc = __builtin_fmaf(bf16_lo(k.z), f[4], acc);
-        acc = __builtin_fmaf(bf16_hi(k.z), f[5], acc);
-        acc = __builtin_fmaf(bf16_lo(k.w), f[6], acc);
-        acc = __builtin_fmaf(bf16_hi(k.w), f[7], acc);
+        // v_dot2c_f32_bf16 (gfx950): bf16 products are exact in fp32, accumulation in fp32
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.x), __builtin_bit_cast(bf16x2_t, raw.x), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.y), __builtin_bit_cast(bf16x2_t, raw.y), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.z), __builtin_bit_cast(bf16x2_t, raw.z), acc, false);
+        acc = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2_t, k.w), __builtin_bit_cast(bf16x2_t, raw.w), acc, false);
         return acc;
     }
 };
