@@ -134,7 +134,7 @@ swa_decode_kernel(DecodeArgs a)
     // The 512-thread instantiation (long caches: the step after a prompt) has 128 registers per
     // lane and keeps twice as many rows in flight in the gathered pass and in the row moves.
     constexpr bool kWide = NT >= 512;
-    constexpr int UV = kWide ? 8 : 4;       // value rows in flight per group (gathered pass)
+    constexpr int UV = kWide ? 6 : 4;       // value rows in flight per group (gathered pass)
     constexpr int SPF = 4;                  // importance values prefetched per thread
 
     extern __shared__ __align__(16) char smem[];
