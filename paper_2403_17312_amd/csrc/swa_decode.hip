@@ -1000,7 +1000,10 @@ swa_decode_kernel(DecodeArgs a)
                     pst += s_wS[v];
                     t += s_acc[v * D + e];
                 }
-                write_out(e, t / pst);
+                // (a budget that keeps no token - no local window and n r below one half - leaves an
+                // empty sum: the output is zero)
+                if (keep > 0) write_out(e, t / pst);
+                else store_elem<AT>(a.out + pair * XROWB, e, 0.f);
             }
         }
 

@@ -173,7 +173,11 @@ __global__ void __launch_bounds__(D) swa_split_merge_kernel(SplitArgs a)
     const int64_t pair = blockIdx.x;
     const int s = (int)(pair / a.h);
     const int keep = a.kept_cnt[s];
-    if (a.ws_ok[pair] == 0 || keep <= 0) return;       // a skipped (full) sequence: nothing is written
+    if (a.ws_ok[pair] == 0) return;                    // a skipped (full) sequence: nothing is written
+    if (keep <= 0) {                                   // a budget that keeps no token: an empty sum
+        store_elem<T>(a.out + pair * ROWB, e, 0.f);
+        return;
+    }
     const float* part = a.ws_part + pair * a.G * (int64_t)(D + 1);
     float t = 0.f, ps = 0.f;
     for (int g = 0; g < a.G; ++g) {

@@ -122,7 +122,9 @@ def prompt_lengths(wl: Workload) -> torch.Tensor:
 
 def heavy_hitter_positions(wl: Workload, seq: int, s: int) -> torch.Tensor:
     """int64 [count] distinct prompt positions of sequence `seq` (host tensor)."""
-    hi = max(1, s - wl.w)
+    # outside the local window where there is one (w < 0 is the even split of Algorithm 1: no fixed window),
+    # and always inside the prompt
+    hi = max(1, min(s, s - max(wl.w, 0)))
     count = min(hi, max(1, int(round(wl.hh_frac * s))))
     g = _gen("cpu", wl.seed, wl.config_id, 202, seq)
     return torch.randperm(hi, generator=g)[:count].sort().values
