@@ -186,6 +186,8 @@ int swa_check_status(const swa_params *params, void *workspace, void *stream, in
  *   keep     = min(m, max(keep_raw, n_local)),  n_global = keep - n_local.
  * w = SWA_W_EVEN_SPLIT is Algorithm 1 line 1 itself: k = nearest integer of n*r/2 (halves
  * round up), w = k and keep_raw = 2k.
+ * Without a local window and with n*r below one half the budget is keep = 0: the decode step then
+ * attends over the empty set, writes out = 0, and leaves an empty cache.
  */
 int swa_budget(int32_t n, int32_t m, int32_t w, int32_t sparsity_bp, int32_t *keep,
                int32_t *n_local, int32_t *n_global);

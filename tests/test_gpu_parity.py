@@ -227,6 +227,46 @@ def test_unordered_window_that_was_widened_keeps_exactly_the_budget(env):
     assert grew > 0, "the case must contain windows with evicted positions"
 
 
+def test_a_budget_that_keeps_no_token_gives_a_zero_output_and_an_empty_cache(env):
+    # no local window (w = 0, or the even split with k = 0) and n r below one half: keep = 0, the sum over
+    # the kept set is empty, the output is zero (as the oracle's) and the cache is empty afterwards
+    O, B, W, LS = env
+    sched = [9900, 9900, 5000, 9999, 9999, 0, 9950, 9000]
+    for form in ["split", "fused", "unordered", "shared", "q8", "window", "lazy"]:
+        for w in (0, B.SWA_W_EVEN_SPLIT):
+            wl = W.Workload("t_keep0", 91, b=3, h=2, d=64, dtype="f16" if form == "q8" else "bf16", prompt_lo=3,
+                            prompt_hi=40, steps=8, w=w, sparsity_bp=9900, hh_frac=0.03)
+            _say(f"  empty budget: {form} w={w}")
+            sp = lambda t: sched[t]
+            if form == "window":
+                rep = LS.run_lockstep_window(wl, 5, sparsity_of_step=sp)
+            elif form == "lazy":
+                rep = LS.run_lockstep(wl, compact_every=3, sparsity_of_step=sp)
+            else:
+                rep = LS.run_lockstep(wl, fused=form != "split", unordered=form in ("unordered", "shared", "q8"),
+                                      head_shared=form == "shared", kv_int8=form == "q8", sparsity_of_step=sp)
+            assert rep.evictions > 0
+    # the call itself: one step on a 5-token cache at 99.99 % sparsity
+    wl = W.Workload("t_keep0_one", 92, b=2, h=2, d=128, dtype="f16", prompt_lo=5, prompt_hi=5, steps=1, w=0,
+                    sparsity_bp=9999, hh_frac=0.03)
+    prompt = W.make_prompt(wl, "cuda", slack="nan")
+    for flags in (0, B.SWA_FUSE_COMPACTION, B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED):
+        st = LS.new_state(wl, dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone()))
+        st.score.zero_()
+        st.params.flags = flags
+        st.out.fill_(7.0)
+        q, kn, vn = W.make_step(wl, 0, prompt["mu"])
+        st.seq_len += 1
+        if flags:
+            st.decode_compact_step(q, kn, vn)
+        else:
+            st.decode_step(q, kn, vn)
+            assert st.kept_cnt.tolist() == [0, 0]
+            st.compact()
+        assert st.check_status() == 0
+        assert st.cache_len.tolist() == [0, 0] and bool((st.out == 0).all())
+
+
 def test_even_split_of_algorithm_1_in_every_step_mode(env):
     # w = SWA_W_EVEN_SPLIT: k = nint(n r / 2) local and k global tokens, recomputed per sequence and step
     O, B, W, LS = env

@@ -508,3 +508,21 @@ def test_kv_footprint_formula_matches_paper_value():
     # the per-pair accounting used by the bench reduces to the same rows
     row_bytes = W.algorithmic_bytes_per_pair(d, 2, 1, 1) - W.algorithmic_bytes_per_pair(d, 2, 0, 0)
     assert row_bytes == 2 * d * 2 + 8 + 4
+
+
+def test_a_budget_of_zero_tokens_leaves_an_empty_sum(oracle):
+    # w = 0 and n r < 1/2: keep = 0.  The kept set is empty, the sum over it is zero, compaction empties the
+    # cache.  (keep = nint(6 * 0.0001) = 0, hand arithmetic.)
+    O = oracle
+    rng = np.random.default_rng(77)
+    b, h, d, cap = 1, 2, 4, 8
+    K = np.zeros((b, h, cap, d)); V = np.zeros((b, h, cap, d))
+    K[:, :, :5], V[:, :, :5] = rng.standard_normal((b, h, 5, d)), rng.standard_normal((b, h, 5, d))
+    score = np.zeros((b, h, cap)); pos = np.full((b, h, cap), -1, dtype=np.int32); pos[:, :, :5] = np.arange(5)
+    cl = np.array([5], dtype=np.int32)
+    assert O.budget(6, 6, 0, 9999) == (0, 0, 0)
+    q, kn, vn = (rng.standard_normal((b, h, d)) for _ in range(3))
+    kept, cnt, out, p = O.decode_step(q, kn, vn, K, V, score, pos, cl, cl + 1, 0, 9999, 0.5)
+    assert cnt[0] == 0 and np.all(out == 0.0) and abs(p[0, 0, :6].sum() - 1.0) < 1e-12
+    O.compact(K, V, score, pos, kept, cnt, cl)
+    assert cl[0] == 0
