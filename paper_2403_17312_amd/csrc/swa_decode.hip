@@ -790,21 +790,27 @@ swa_decode_kernel(DecodeArgs a)
                     const int i = lo + k;
                     if (i >= hi) break;
                     const bool kept = (keptm >> k) & 1ull;
+                    // the evicted slots are listed in ascending order (a fixed order: the subtractive
+                    // output adds them up in list order, and the result must not depend on timing)
                     if (i < keep) {
                         if (kept) {
                             s_src[i] = (uint16_t)i;
                         } else {
                             if (hr < a.lds_slots / 2) s_holes[hr] = (uint16_t)i;
+                            if (fused && hr < kMaxFix) s_evict[hr] = i;
                             ++hr;
                         }
                     } else if (kept) {
                         if (mr < a.lds_slots / 2) s_movers[mr] = (uint16_t)i;
                         ++mr;
+                    } else if (fused) {
+                        const int e = run_h + (i - keep) - mr;
+                        if (e >= 0 && e < kMaxFix) s_evict[e] = i;
                     }
-                    if (fused && !kept) {
-                        const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
-                        if (e < kMaxFix) s_evict[e] = i;
-                    }
+                }
+                if (fused && tid == 0) {
+                    const int ne = run_h + (m - keep) - run_m;
+                    s_ecnt = ne < 0 ? 0 : (ne > kMaxFix ? kMaxFix : ne);
                 }
                 __syncthreads();
                 n_moves = run_h < run_m ? run_h : run_m;
@@ -854,9 +860,13 @@ swa_decode_kernel(DecodeArgs a)
                 if ((keptm >> k) & 1ull) {
                     s_kept[out_pos++] = (uint16_t)i;
                 } else if (fused) {
-                    const int e = atomicAdd(&s_ecnt, 1);   // at most E <= kMaxFix entries
+                    const int e = i - out_pos;             // evicted slots before this one: ascending list
                     if (e < kMaxFix) s_evict[e] = i;
                 }
+            }
+            if (fused && tid == 0) {
+                const int ne = m - out_total;
+                s_ecnt = ne < 0 ? 0 : (ne > kMaxFix ? kMaxFix : ne);
             }
             __syncthreads();
             if (kout)

@@ -1036,6 +1036,47 @@ def test_hip_graph_replays_equal_the_eager_run(env, form):
     assert st.check_status() == 0
 
 
+def test_a_few_evictions_at_once_give_the_same_bits_on_every_run(env):
+    # 2..8 evictions in one step take the subtractive output, which adds the evicted rows up in list
+    # order: the list must come out in a fixed order (ascending slots), or the output's last bits depend
+    # on which wave wrote first.  Four states step the same trajectory; a budget that tightens by a few
+    # tokens every other step keeps the step on that path.
+    O, B, W, LS = env
+    for dtype, flags in [("f32", B.SWA_FUSE_COMPACTION | B.SWA_UNORDERED), ("f16", B.SWA_FUSE_COMPACTION), ("bf16", 0)]:
+        wl = W.Workload(f"t_det_few_{dtype}", 19, b=4, h=5, d=128, dtype=dtype, prompt_lo=73, prompt_hi=301, steps=14, w=5,
+                        sparsity_bp=3000, hh_frac=0.02)
+        sched = [3000, 3100, 3100, 3250, 3250, 3400, 3400, 3600, 3600, 3800, 3800, 4000, 4000, 4100]
+        prompt = W.make_prompt(wl, "cuda", slack="nan")
+        inputs = [W.make_step(wl, t, prompt["mu"]) for t in range(wl.steps)]
+        runs, few = [], 0
+        for rep in range(4):
+            st = LS.new_state(wl, dict(prompt, K=prompt["K"].clone(), V=prompt["V"].clone(), pos=prompt["pos"].clone()),
+                              debug_probs=(rep % 2 == 0))
+            st.score.zero_()
+            st.params.flags = flags
+            outs = []
+            for t in range(wl.steps):
+                st.params.sparsity_bp = sched[t]
+                q, kn, vn = inputs[t]
+                st.seq_len += 1
+                before = st.cache_len.clone()
+                if flags:
+                    st.decode_compact_step(q, kn, vn, want_idx=(rep < 2))
+                else:
+                    st.decode_step(q, kn, vn)
+                    st.compact()
+                if rep == 0:
+                    ev = (before + 1 - st.cache_len)
+                    few += int(((ev >= 2) & (ev <= 8)).sum())
+                outs.append(st.out.clone())
+            assert st.check_status() == 0
+            runs.append((torch.stack(outs), st.cache_len.clone(), st.score.clone()))
+        assert few >= 8, "the schedule must produce steps with 2..8 evictions"
+        for r in runs[1:]:
+            assert torch.equal(r[1], runs[0][1])
+            assert torch.equal(r[0].view(torch.uint8), runs[0][0].view(torch.uint8)), f"{dtype}: outputs differ between runs"
+
+
 def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
     O, B, W, LS = env
     wl = W.Workload("t_det", 15, b=4, h=6, d=128, dtype="f16", prompt_lo=100, prompt_hi=400,
