@@ -161,6 +161,11 @@ def prompt_of(wl, W):
     return _PROMPTS[key]
 
 
+# Device memory stays with torch's caching allocator for the whole process: a serving stack allocates its
+# caches once, and memory handed back to the driver and acquired again between workloads measured 1.5-3 %
+# slower on this GPU than the blocks of the first allocation.
+
+
 def replicas_for(step_bytes):
     """Replica count from bytes alone: the R steps of one sweep touch R x (one step's working set) of
     distinct memory, which must reach SWEEP_MIN_BYTES even for the lightest step; at least two."""
@@ -351,7 +356,6 @@ def bench_workload(wl, steps, warmup, mode, torch, B, W, fused=True, want_kernel
             sb = [step_bytes[i // n] for i in timed if i // n > 0]
             res["decode_steady_gbs"] = sum(sb) / (sum(steady) * 1e-3) / 1e9
         del reps
-    torch.cuda.empty_cache()
     return res
 
 
@@ -399,7 +403,6 @@ def prewarm(torch, B, seconds):
         torch.cuda.synchronize()
         n += 16
     del x
-    torch.cuda.empty_cache()
     return n
 
 
@@ -417,7 +420,6 @@ def stream_read_ceiling(torch, B):
         ms = e0.elapsed_time(e1)
         best = ms if best is None else min(best, ms)
     del x
-    torch.cuda.empty_cache()
     return (1 << 32) / (best * 1e-3) / 1e9
 
 
@@ -532,6 +534,42 @@ def summary_of(res, step_mode, kv_int8, wl_name):
                                            "avg_launch_ms", "first_step_frac", "steady_frac")}}
 
 
+def other_workload_in_a_process_of_its_own(name, args):
+    """Times one further workload by running this script on it in a child process (whole trajectories, the same
+    step forms), before this process has touched the GPU.  Memory that a process acquires late, after
+    gigabytes were allocated and released, measured 2-3 % slower on this GPU than the first allocations of a
+    fresh process; one workload per process keeps every figure on the same footing as the headline's and as
+    the rocprofv3 runs under profiles/, which are one workload per process too.  Returns the entry for
+    other_workloads, or None (the caller then times the workload in-process)."""
+    import subprocess
+    cmd = [sys.executable, os.path.abspath(__file__), "--gpus", "1", "--config", name, "--others", "none",
+           "--no-cpu-baseline", "--ordered-forms", args.ordered_forms, "--step-mode", args.step_mode, "--mode", args.mode,
+           "--prewarm-s", str(args.prewarm_s), "--compact-every", str(args.compact_every)]
+    if args.kv_int8:
+        cmd.append("--kv-int8")
+    if args.split_rows:
+        cmd.append("--split-rows")
+    try:
+        out = subprocess.run(cmd, capture_output=True, text=True, timeout=600)
+        c = json.loads(out.stdout.strip().splitlines()[-1])
+    except Exception:
+        return None
+    entry = {"workload": name, "step_mode": args.step_mode, "steps": c["steps"], "replicas": c["config"]["replicas"],
+             "cold": c["config"]["cold"], "kv_tokens_per_s": c["value"], "ms_per_step": c["ms_per_step"],
+             "decode_kernel_ms_avg": c["detail"].get("decode_kernel_ms_avg"),
+             "compact_kernel_ms_avg": c["detail"].get("compact_kernel_ms_avg"),
+             "whole_step_alg_gbs": c["whole_step_alg_gbs"], "prefill_seed_ms": c["detail"].get("prefill_seed_ms"),
+             "roofline": {k: c["roofline"].get(k) for k in ("bound", "achieved", "peak", "unit", "frac", "traffic",
+                                                            "alg_bytes_per_launch", "avg_launch_ms", "first_step_frac",
+                                                            "steady_frac")},
+             "measured_in": "a process of its own"}
+    if c["detail"].get("prefill_seed"):
+        entry["prefill_seed"] = c["detail"]["prefill_seed"]
+    if c.get("other_step_forms"):
+        entry["other_step_forms"] = c["other_step_forms"]
+    return entry
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -567,6 +605,8 @@ def main():
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
     ap.add_argument("--others", default="c5_llama7b_sp50,c5_llama7b_sp90,c4_opt30b,c3_opt13b,c2_opt6p7b",
                     help="comma list of further workloads summarised in the same line ('none' = none)")
+    ap.add_argument("--others-in-process", action="store_true",
+                    help="time the further workloads in this process instead of one child process each")
     ap.add_argument("--no-whole-trajectory", action="store_true",
                     help="with --steps: do not also time whole trajectories of the headline workload")
     ap.add_argument("--ordered-forms", default="fused,split",
@@ -577,6 +617,21 @@ def main():
               "(the path shards over (sequence, head) pairs with no exchange between GPUs)",
               file=sys.stderr)
         sys.exit(2)
+
+    # the other workloads first, each in a process of its own, while this process has not touched the GPU
+    none = ("", "none")
+    other_names = [x for x in args.others.split(",") if x not in none and x != args.config]
+    child_entries = {}
+    whole_child = None
+    if not args.others_in_process:
+        for name in other_names:
+            child_entries[name] = other_workload_in_a_process_of_its_own(name, args)
+        if args.steps is not None and not args.no_whole_trajectory:
+            # the headline workload over whole trajectories, on the same footing
+            saved = args.ordered_forms
+            args.ordered_forms = "none"
+            whole_child = other_workload_in_a_process_of_its_own(args.config, args)
+            args.ordered_forms = saved
 
     import torch
     from paper_2403_17312_amd import binding as B
@@ -656,9 +711,12 @@ def main():
     # --steps covers a short stretch of the trajectory: the same workload over whole trajectories (the step
     # after the prompt included, at its true weight), for reference
     if args.steps is not None and not args.no_whole_trajectory and res["steps"] < wl.steps * res["replicas"]:
-        r = bench_workload(wl, None, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
-                           kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
-        line["whole_trajectory"] = summary_of(r, args.step_mode, args.kv_int8, wl.name)
+        if whole_child is not None:
+            line["whole_trajectory"] = {k: v for k, v in whole_child.items() if k != "workload"}
+        else:
+            r = bench_workload(wl, None, warmup, args.mode, torch, B, W, fused=fused_of(args.step_mode),
+                               kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
+            line["whole_trajectory"] = summary_of(r, args.step_mode, args.kv_int8, wl.name)
         if line["roofline"]["first_step_frac"] is None:      # the timed stretch held no step after a prompt
             line["roofline"]["first_step_frac"] = line["whole_trajectory"]["roofline"]["first_step_frac"]
             line["roofline"]["first_step_gbs"] = line["whole_trajectory"]["roofline"]["first_step_frac"] * HBM_PEAK_GBS
@@ -676,11 +734,14 @@ def main():
         line["cpu_baseline"] = cpu_baseline(wl, W, torch)
 
     others = []
-    for name in [x for x in args.others.split(",") if x not in none and x != args.config]:
+    for name in other_names:
         o = W.CONFIGS[name]
         if args.kv_int8 and o.dtype != "f16":
             continue
-        entry = {"workload": name}
+        if child_entries.get(name) is not None:
+            others.append(child_entries[name])
+            continue
+        entry = {"workload": name, "measured_in": "this process, after the headline workload"}
         for sm in [args.step_mode] + extra_forms:
             r = bench_workload(o, None, min(o.steps, 8), args.mode, torch, B, W, fused=fused_of(sm),
                                kv_int8=args.kv_int8, compact_every=args.compact_every, split_rows=args.split_rows)
