@@ -406,6 +406,54 @@ def prewarm(torch, B, seconds):
     return n
 
 
+def bench_offload_tier(wl, torch, B, W, steps=4):
+    """swa_offload_evicted between swa_decode_step and swa_compact_kv (Section V-A, Algorithm 2, the store half of
+    the GPU-CPU caching phase): the step after the prompt evicts most of the prompt, the following ones one
+    token per pair.  Rows cross the host link, so the bound is that link (PCIe 5.0 x16: 64 GB/s per direction),
+    not HBM; this is the PCIe-inclusive leg and never part of `value`.  Then a reload of 64 tokens per pair."""
+    prompt = prompt_of(wl, W)
+    params = B.make_params(wl.b, wl.h, wl.d, wl.cap, wl.w, wl.sparsity_bp, wl.torch_dtype)
+    st = B.DecodeState(params, device="cuda", debug_probs=False)
+    st.K.copy_(prompt["K"]); st.V.copy_(prompt["V"]); st.pos.copy_(prompt["pos"])
+    st.cache_len.copy_(prompt["cache_len"]); st.seq_len.copy_(prompt["cache_len"])
+    store = B.HostStore(params, host_cap=wl.prompt_hi + steps)
+    row_bytes = 2 * wl.d * wl.elem_bytes + 8                      # K row, V row, importance, position
+    out = []
+    for t in range(steps):
+        q, kn, vn = W.make_step(wl, t, prompt["mu"])
+        st.seq_len += 1
+        st.decode_step(q, kn, vn)
+        before = int(store.len.sum())
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        B.swa_offload_evicted(params, st.K, st.V, st.score, st.pos, st.kept_idx, st.kept_cnt, st.cache_len, store,
+                              st.workspace)
+        e1.record()
+        torch.cuda.synchronize()
+        rows = int(store.len.sum()) - before
+        ms = e0.elapsed_time(e1)
+        out.append({"step": t, "tokens": rows, "bytes": rows * row_bytes, "ms": ms, "gbs": rows * row_bytes / (ms * 1e-3) / 1e9})
+        st.compact()
+    # load the 64 oldest stored tokens of every pair back
+    n_req = int(min(64, int(store.len.min())))
+    req = torch.arange(n_req, dtype=torch.int32, device="cuda").expand(wl.b, wl.h, n_req).contiguous()
+    cnt = torch.full((wl.b,), n_req, dtype=torch.int32, device="cuda")
+    new_len = torch.zeros_like(st.cache_len)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    B.swa_reload_tokens(params, store, req, cnt, max(n_req, 1), st.K, st.V, st.score, st.pos, st.cache_len, new_len,
+                        st.workspace)
+    e1.record()
+    torch.cuda.synchronize()
+    assert st.check_status() == 0
+    ms = e0.elapsed_time(e1)
+    nbytes = n_req * wl.b * wl.h * row_bytes
+    return {"bound": "host link", "peak_gbs": 64.0, "offload_steps": out,
+            "frac_first_step": out[0]["gbs"] / 64.0,
+            "reload": {"tokens": n_req * wl.b * wl.h, "bytes": nbytes, "ms": ms, "gbs": nbytes / (ms * 1e-3) / 1e9},
+            "note": "device-initiated copies to and from pinned host memory; events on the launch stream"}
+
+
 def stream_read_ceiling(torch, B):
     """Streaming-read rate of this GPU on a 4 GiB buffer (plain 128-bit loads, nothing else)."""
     x = torch.ones((1 << 30,), dtype=torch.float32, device="cuda")
@@ -600,6 +648,8 @@ def main():
                     help="also time swa_prefill_attention over the workload's prompts")
     ap.add_argument("--prewarm-s", type=float, default=1.5,
                     help="seconds of plain streaming reads before anything is timed (0 = none)")
+    ap.add_argument("--offload-tier", action="store_true",
+                    help="also time swa_offload_evicted / swa_reload_tokens on the workload (host link, not HBM)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run plain 1 GiB device copies (known traffic, for scaling rocprofv3 counters)")
@@ -707,6 +757,8 @@ def main():
         line["detail"]["prefill_seed"] = seed_detail(wl, res)
     if args.prefill_attention:
         line["detail"]["prefill_attention"] = bench_prefill_attention(wl, torch, B, W)
+    if args.offload_tier:
+        line["detail"]["offload_tier"] = bench_offload_tier(wl, torch, B, W)
 
     # --steps covers a short stretch of the trajectory: the same workload over whole trajectories (the step
     # after the prompt included, at its true weight), for reference
