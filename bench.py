@@ -25,7 +25,7 @@ stretch of the steady state (W >= R puts every replica's step after the prompt
 into the warm-up); the whole-trajectory figures, with the first step's own rate,
 are printed beside it in `whole_trajectory`.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line.
 """
 from __future__ import annotations
 
@@ -517,14 +517,25 @@ def cpu_baseline(wl, W, torch, budget_s=10.0):
     }
 
 
-def load_traffic(name):
+def load_traffic(name, alg_bytes):
+    """The counter record of this workload and step form whose timed launches are the ones timed here: the
+    records are keyed by workload (whole trajectories) or workload + "_steps<K>" (a stretch of K steps), and the
+    one whose algorithmic bytes per launch agree with this run's to 2 % is taken; none agreeing: no figure."""
     path = os.path.join(ROOT, "profiles", "pmc_traffic.json")
     if not os.path.exists(path):
         return None
     try:
-        return json.load(open(path)).get(name)
+        records = json.load(open(path))
     except Exception:
         return None
+    best = None
+    for key, rec in records.items():
+        if key != name and not key.startswith(name + "_steps"):
+            continue
+        err = abs(rec["algorithmic_bytes_per_launch"] - alg_bytes) / alg_bytes
+        if err <= 0.02 and (best is None or err < best[0]):
+            best = (err, dict(rec, record=key))
+    return best[1] if best else None
 
 
 STEP_TEXT = {
@@ -548,7 +559,7 @@ def roofline_of(res, step_mode, kv_int8, wl_name):
     dec_ms = res["ms_per_step"] if one_kernel else res["decode_kernel_ms_avg"]
     achieved = res["alg_bytes_per_step"] / (dec_ms * 1e-3) / 1e9
     tag = ("" if step_mode == "unordered" else "_" + step_mode) + ("_q8" if kv_int8 else "")
-    traffic = load_traffic(wl_name + tag) if one_kernel else None
+    traffic = load_traffic(wl_name + tag, res["alg_bytes_per_step"]) if one_kernel else None
     # one-kernel forms: the step is the kernel, so the timed region's own split applies; two calls: the
     # per-launch event brackets (which read a few microseconds low: an empty bracket costs more than a full one)
     first_gbs = res.get("first_step_gbs") if one_kernel else res.get("decode_first_step_gbs")
@@ -560,8 +571,8 @@ def roofline_of(res, step_mode, kv_int8, wl_name):
         "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
         "traffic": (traffic["fetch_bytes_per_launch"] + traffic["write_bytes_per_launch"]) if traffic else None,
         "traffic_source": ("profiles/pmc_traffic.json: rocprofv3 --pmc FETCH_SIZE and --pmc WRITE_SIZE runs of this "
-                           "workload and step form, whole trajectories, scaled by a 1 GiB copy (not measured in "
-                           "this run)") if traffic else None,
+                           "workload, step form and timed steps (record `traffic_detail.record`), scaled by a "
+                           "1 GiB copy (not measured in this run)") if traffic else None,
         "traffic_detail": traffic,
         "alg_bytes_per_launch": res["alg_bytes_per_step"], "avg_launch_ms": dec_ms,
         "timing": ("HIP events around the timed region on the launch stream / launches" if one_kernel
