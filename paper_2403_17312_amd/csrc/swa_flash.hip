@@ -39,6 +39,17 @@ __device__ __forceinline__ uint32_t half_of(const Vec16& v, int e)
     return (w[e >> 1] >> ((e & 1) * 16)) & 0xffffu;
 }
 
+// x of lane (l % 32) and x of lane (l % 32) + 32, in every lane: v_permlane32_swap exchanges the
+// upper half of one register with the lower half of another, so two copies of x come back as
+// (the lower half's x, the upper half's x) - no trip through LDS.
+__device__ __forceinline__ void both_halves(float x, float& lo, float& hi)
+{
+    const uint32_t u = __float_as_uint(x);
+    const auto r = __builtin_amdgcn_permlane32_swap(u, u, false, false);
+    lo = __uint_as_float(r[0]);
+    hi = __uint_as_float(r[1]);
+}
+
 // Two fp32 values rounded to T, packed into one dword.
 template <typename T>
 __device__ __forceinline__ uint32_t pack2(float f0, float f1);
@@ -74,6 +85,11 @@ swa_flash_prefill_kernel(FlashArgs a)
     constexpr int CPR = ROWB / 16;      // 16-byte chunks per cache row
     constexpr int LD = BK * CPR / NT;   // chunks per thread, per tensor and tile
     constexpr bool kPaired = EB == 2 && LD == 2;
+#ifndef SWA_FLASH_PF
+#define SWA_FLASH_PF 3
+#endif
+    constexpr float kSlack = 8.f;
+    constexpr int PF = SWA_FLASH_PF;    // LDS fragment reads in flight ahead of the product that uses them
     constexpr int NBUF = (EB == 4 && D == 128) ? 1 : 2;   // LDS buffers (64 KB of static LDS at most)
     static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
 
@@ -141,8 +157,10 @@ swa_flash_prefill_kernel(FlashArgs a)
             const int j = tile_key(x), cc = tid % CPR;
             int row = kt * BK + j;
             row = row < s ? row : s - 1;          // rows past the prompt are masked; keep them finite
-            gk[x] = load16(Kp + (int64_t)row * ROWB + cc * 16);
-            gv[x] = load16(Vp + (int64_t)row * ROWB + cc * 16);
+            // uniform base + 32-bit offset (a pair's rows span less than 4 GiB: checked by the launcher)
+            const uint32_t off = (uint32_t)row * ROWB + cc * 16;
+            gk[x] = load16(Kp + off);
+            gv[x] = load16(Vp + off);
         }
     };
     // key j is element i16 of half-wave hbk's 16 keys: its place (in elements) in a channel's
@@ -160,10 +178,11 @@ swa_flash_prefill_kernel(FlashArgs a)
         for (int x = 0; x < LD; ++x) store16(s_k[buf] + tile_key(x) * KSTR + cc * 16, gk[x]);
         if constexpr (kPaired) {
             const int posk = key_slot(tile_key(0));      // even, and key_slot(tile_key(1)) == posk + 1
+            const uint32_t w0[4] = {gv[0].x, gv[0].y, gv[0].z, gv[0].w}, w1[4] = {gv[1].x, gv[1].y, gv[1].z, gv[1].w};
 #pragma unroll
-            for (int e = 0; e < 8; ++e)
+            for (int e = 0; e < 8; ++e)      // channel e of the even key below, of its successor above: one byte permute
                 *reinterpret_cast<uint32_t*>(s_vt[buf] + vt_row(cc * 8 + e) + posk * 2) =
-                    half_of(gv[0], e) | (half_of(gv[1], e) << 16);
+                    __builtin_amdgcn_perm(w1[e >> 1], w0[e >> 1], (e & 1) ? 0x07060302u : 0x05040100u);
         } else if constexpr (EB == 2) {
 #pragma unroll
             for (int x = 0; x < LD; ++x) {
@@ -193,6 +212,11 @@ swa_flash_prefill_kernel(FlashArgs a)
 
     gload(0);
     lstore(0);
+    // Every load issued so far (the query fragments among them) is waited for HERE, once: the
+    // memory counter is in-order, so a query fragment still in flight at the loop's entry would
+    // make the compiler wait, inside every iteration's first product, for counts that on all
+    // later iterations mean "the tile just requested has arrived" - the prefetch would be lost.
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0)
     __syncthreads();
     for (int kt = 0; kt < nkt; ++kt) {
         const int buf = kt % NBUF;
@@ -202,8 +226,17 @@ swa_flash_prefill_kernel(FlashArgs a)
 #pragma unroll
             for (int i = 0; i < 16; ++i) c[i] = 0.f;
             const char* kb = s_k[buf] + l32 * KSTR + hb * 16;
+            // key fragments are read from LDS PF products ahead of their use, in this order
+            Vec16 kf[NV];
 #pragma unroll
-            for (int v = 0; v < NV; ++v) c = Mfma<T>::run(load16(kb + v * 32), qv[v], c);   // C[key][query]
+            for (int v = 0; v < PF && v < NV; ++v) kf[v] = load16(kb + v * 32);
+#pragma unroll
+            for (int v = 0; v < NV; ++v) {
+                if (v + PF < NV) kf[v + PF] = load16(kb + (v + PF) * 32);
+                __builtin_amdgcn_sched_barrier(0);
+                c = Mfma<T>::run(kf[v], qv[v], c);   // C[key][query]
+                __builtin_amdgcn_sched_barrier(0);
+            }
             // only the tiles that reach the wave's diagonal need the causal mask
             if (kt * BK + BK - 1 > w_lo) {
 #pragma unroll
@@ -215,11 +248,16 @@ swa_flash_prefill_kernel(FlashArgs a)
             float mx = c[0];
 #pragma unroll
             for (int i = 1; i < 16; ++i) mx = fmaxf(mx, c[i]);
-            mx = fmaxf(mx, __shfl_xor(mx, 32, kWave)) * a.scale_log2e;     // scale > 0: max commutes
-            // tile 0 holds key 0, visible to every query, so the running maximum is finite from
-            // the first tile on
-            const float m_new = fmaxf(m, mx);
-            const float alpha = __builtin_amdgcn_exp2f(m - m_new);     // 0 on the first tile
+            float mx_lo, mx_hi;
+            both_halves(mx, mx_lo, mx_hi);
+            mx = fmaxf(mx_lo, mx_hi) * a.scale_log2e;     // scale > 0: max commutes
+            // tile 0 holds key 0, visible to every query, so the reference maximum is finite from
+            // the first tile on.  The reference only has to bound the exponents, not equal the true
+            // maximum (out = o / l whatever it is): it follows the tile maximum only when that
+            // exceeds it by more than kSlack powers of two, so the weights stay below 2^kSlack and
+            // the running output is rescaled a few times per query instead of at every new maximum.
+            const float m_new = (mx > m + kSlack) ? mx : m;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_new);     // 0 on the first tile, else mostly 1
             float p[16];
             float ps = 0.f;
 #pragma unroll
@@ -239,11 +277,19 @@ swa_flash_prefill_kernel(FlashArgs a)
             Vec16 pv[NP];
 #pragma unroll
             for (int v = 0; v < NP; ++v) pv[v] = pack<T>(p + v * EPV);
+            // value fragments likewise: fragment f = ct * NP + v, read PF products ahead
+            Vec16 vf[CT * NP];
+            // vt_row(32 ct + l32) = vt_row(l32) + ct (32 VSTR + 32): one lane address, constant offsets
+            const char* vb0 = s_vt[buf] + vt_row(l32) + hb * 16;
+            auto vfrag = [&](int f) { return load16(vb0 + (f / NP) * (32 * VSTR + 32) + (f % NP) * 32); };
 #pragma unroll
-            for (int ct = 0; ct < CT; ++ct) {
-                const char* vb = s_vt[buf] + vt_row(ct * 32 + l32) + hb * 16;
+            for (int f = 0; f < PF && f < CT * NP; ++f) vf[f] = vfrag(f);
 #pragma unroll
-                for (int v = 0; v < NP; ++v) o[ct] = Mfma<T>::run(load16(vb + v * 32), pv[v], o[ct]);   // C[channel][query]
+            for (int f = 0; f < CT * NP; ++f) {
+                if (f + PF < CT * NP) vf[f + PF] = vfrag(f + PF);
+                __builtin_amdgcn_sched_barrier(0);
+                o[f / NP] = Mfma<T>::run(vf[f], pv[f % NP], o[f / NP]);   // C[channel][query]
+                __builtin_amdgcn_sched_barrier(0);
             }
         }
         if constexpr (NBUF == 1) __syncthreads();      // every wave is done with the only buffer
@@ -251,7 +297,9 @@ swa_flash_prefill_kernel(FlashArgs a)
         __syncthreads();
     }
 
-    l += __shfl_xor(l, 32, kWave);
+    float l_lo, l_hi;
+    both_halves(l, l_lo, l_hi);
+    l = l_lo + l_hi;
     if (t < s) {
         const float inv = 1.f / l;
 #pragma unroll

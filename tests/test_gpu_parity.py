@@ -1,4 +1,5 @@
 """GPU parity tests: the HIP library (through its C ABI) against the fp64 oracle."""
+import math
 import numpy as np
 import pytest
 import torch
@@ -1107,9 +1108,10 @@ def test_slack_slots_are_never_touched_and_runs_are_deterministic(env):
         assert torch.equal(a[3][s, :, :L], b_[3][s, :, :L])
 
 
-@pytest.mark.parametrize("dtype,d", [("f16", 128), ("bf16", 128), ("f16", 64), ("bf16", 64), ("f32", 128),
-                                     ("f32", 64)])
-def test_prefill_attention_matches_the_oracle(env, dtype, d):
+@pytest.mark.parametrize("dtype,d,logits", [("f16", 128, "random"), ("bf16", 128, "random"), ("f16", 64, "random"),
+                                            ("bf16", 64, "random"), ("f32", 128, "random"), ("f32", 64, "random"),
+                                            ("f16", 128, "rising"), ("bf16", 128, "rising"), ("f32", 64, "rising")])
+def test_prefill_attention_matches_the_oracle(env, dtype, d, logits):
     # dense causal attention over the prompt (Eq. 1-2) on MFMA, plus the importance seed.
     # Tolerance from the arithmetic: the weights are rounded once to the cache dtype before the
     # second product (unit roundoff u = 2^-11 fp16, 2^-8 bf16), values are exact, sums are fp32,
@@ -1123,9 +1125,15 @@ def test_prefill_attention_matches_the_oracle(env, dtype, d):
                     steps=2, w=4, sparsity_bp=8000, hh_frac=0.02)
     prompt = W.make_prompt(wl, "cuda", slack="nan")
     g = torch.Generator(device="cuda").manual_seed(77)
+    # "rising": every query's logits grow with the key position, by about 40 powers of two over the longest
+    # prompt and in steps of every size, so the running maximum of the streaming softmax moves at every tile
+    axis = torch.nn.functional.normalize(torch.randn((wl.h, 1, d), generator=g, device="cuda"), dim=-1)
     for s_i, L in enumerate(lens):           # fixed lengths that straddle the tile and block sizes
         k = torch.randn((wl.h, L, d), generator=g, device="cuda")
         v = torch.randn((wl.h, L, d), generator=g, device="cuda")
+        if logits == "rising":
+            ramp = torch.arange(L, device="cuda", dtype=torch.float32) / 417.0
+            k = 0.25 * k + (40.0 * math.log(2.0) / (4.0 * wl.scale)) * ramp[None, :, None] * axis
         prompt["K"][s_i] = float("nan")
         prompt["V"][s_i] = float("nan")
         prompt["K"][s_i, :, :L] = k.to(wl.torch_dtype)
@@ -1133,7 +1141,10 @@ def test_prefill_attention_matches_the_oracle(env, dtype, d):
     cache_len = torch.tensor(lens, dtype=torch.int32, device="cuda")
     Q = torch.full((wl.b, wl.h, wl.cap, d), float("nan"), dtype=wl.torch_dtype, device="cuda")
     for s_i, L in enumerate(lens):
-        Q[s_i, :, :L] = (1.5 * torch.randn((wl.h, L, d), generator=g, device="cuda")).to(wl.torch_dtype)
+        qf = 1.5 * torch.randn((wl.h, L, d), generator=g, device="cuda")
+        if logits == "rising":
+            qf = 0.25 * qf + 4.0 * axis
+        Q[s_i, :, :L] = qf.to(wl.torch_dtype)
     out = torch.full_like(Q, 7.0)
     R = 5
     score = torch.full((wl.b, wl.h, wl.cap), float("nan"), dtype=torch.float32, device="cuda")
