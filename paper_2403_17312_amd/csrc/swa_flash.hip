@@ -85,11 +85,8 @@ swa_flash_prefill_kernel(FlashArgs a)
     constexpr int CPR = ROWB / 16;      // 16-byte chunks per cache row
     constexpr int LD = BK * CPR / NT;   // chunks per thread, per tensor and tile
     constexpr bool kPaired = EB == 2 && LD == 2;
-#ifndef SWA_FLASH_PF
-#define SWA_FLASH_PF 3
-#endif
-    constexpr float kSlack = 8.f;
-    constexpr int PF = SWA_FLASH_PF;    // LDS fragment reads in flight ahead of the product that uses them
+    constexpr float kSlack = 8.f;       // how far (powers of two) a tile maximum may exceed the reference maximum
+    constexpr int PF = 3;               // LDS fragment reads in flight ahead of the product that uses them
     constexpr int NBUF = (EB == 4 && D == 128) ? 1 : 2;   // LDS buffers (64 KB of static LDS at most)
     static_assert(LD >= 1 && BK * CPR % NT == 0, "tile must split evenly over the workgroup");
 
@@ -281,14 +278,16 @@ swa_flash_prefill_kernel(FlashArgs a)
             Vec16 vf[CT * NP];
             // vt_row(32 ct + l32) = vt_row(l32) + ct (32 VSTR + 32): one lane address, constant offsets
             const char* vb0 = s_vt[buf] + vt_row(l32) + hb * 16;
-            auto vfrag = [&](int f) { return load16(vb0 + (f / NP) * (32 * VSTR + 32) + (f % NP) * 32); };
+            // product f works on channel tile f % CT with weight fragment f / CT: consecutive products
+            // accumulate into different tiles, so none waits for the one before it
+            auto vfrag = [&](int f) { return load16(vb0 + (f % CT) * (32 * VSTR + 32) + (f / CT) * 32); };
 #pragma unroll
             for (int f = 0; f < PF && f < CT * NP; ++f) vf[f] = vfrag(f);
 #pragma unroll
             for (int f = 0; f < CT * NP; ++f) {
                 if (f + PF < CT * NP) vf[f + PF] = vfrag(f + PF);
                 __builtin_amdgcn_sched_barrier(0);
-                o[f / NP] = Mfma<T>::run(vf[f], pv[f % NP], o[f / NP]);   // C[channel][query]
+                o[f % CT] = Mfma<T>::run(vf[f], pv[f / CT], o[f % CT]);   // C[channel][query]
                 __builtin_amdgcn_sched_barrier(0);
             }
         }
