@@ -154,7 +154,7 @@ swa_flash_prefill_kernel(FlashArgs a)
             const int j = tile_key(x), cc = tid % CPR;
             int row = kt * BK + j;
             row = row < s ? row : s - 1;          // rows past the prompt are masked; keep them finite
-            // uniform base + 32-bit offset (a pair's rows span less than 4 GiB: checked by the launcher)
+            // uniform base + 32-bit offset (cap <= SWA_MAX_CAP keeps a pair's rows within 8 MiB)
             const uint32_t off = (uint32_t)row * ROWB + cc * 16;
             gk[x] = load16(Kp + off);
             gv[x] = load16(Vp + off);
